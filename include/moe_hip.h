@@ -1,0 +1,170 @@
+/*
+ * moe_hip.h -- C ABI of the one-GPU MoE-layer hot path (MI355X / gfx950).
+ *
+ * The library computes one GPU's share of an MoE layer's training step, i.e. the
+ * MoE layer of Eq. 3 of the paper
+ *     MoE(x) = sum_{i in argtopk(g(x))} g(x)_i * f(x W_i^A) W_i^B
+ * with the expert body of Eq. 1 (FFN(x) = f(x W^A) W^B) read as SwiGLU
+ * (W^A = (Wg, Wu), f(x W^A) = silu(x Wg) * (x Wu), W^B = Wd), without token
+ * dropping (evaluation setup of the paper: every assignment is computed), for
+ * tokens whose experts are all local (the local branch of the paper's token
+ * dispatching, Algorithm 3), and its backward pass.
+ *
+ * Conventions common to every entry point
+ *  - Every pointer is a DEVICE pointer owned by the caller unless it says "host".
+ *    The library never allocates, frees or keeps a pointer past the call.
+ *  - All tensors are dense row-major; base pointers must be 16-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call
+ *    only enqueues kernels on that stream and returns without synchronising.
+ *  - dtype MOE_F32: X, weights, activations, outputs and weight gradients are fp32.
+ *    dtype MOE_BF16: they are bfloat16 (round-to-nearest-even at every store),
+ *    products accumulate in fp32.  Logits, combine weights and their gradient are
+ *    always fp32; all index arrays are int32.
+ *  - Return value: MOE_OK, or a negative error code; on error nothing was launched
+ *    and moe_last_error() describes the reason (thread-local, host string).
+ *  - Calls on one stream are ordered; two calls that share a workspace must not
+ *    overlap.
+ */
+#ifndef MOE_HIP_H
+#define MOE_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_ABI_VERSION 1
+
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+enum { MOE_GATE_SOFTMAX = 0, MOE_GATE_SIGMOID = 1 };
+enum {
+  MOE_OK = 0,
+  MOE_EINVAL = -1,  /* null pointer, bad shape, bad alignment */
+  MOE_EWS = -2,     /* workspace too small */
+  MOE_EDTYPE = -3,  /* unknown dtype / gate */
+  MOE_ELAUNCH = -4  /* the HIP runtime refused a launch */
+};
+
+/* Shape of the routed part of one MoE layer on this GPU. */
+typedef struct moe_shape {
+  int32_t T;      /* tokens on this GPU                                  (>= 0) */
+  int32_t d;      /* hidden size; multiple of 8                                  */
+  int32_t E;      /* routed experts, 1..MOE_MAX_EXPERTS                          */
+  int32_t k;      /* experts per token, 1..min(E, MOE_MAX_TOPK)                  */
+  int32_t d_ff;   /* expert width; multiple of 8                                 */
+  int32_t dtype;  /* MOE_F32 or MOE_BF16                                         */
+  int32_t gate;   /* MOE_GATE_SOFTMAX (over all E logits) or MOE_GATE_SIGMOID    */
+  int32_t renorm; /* 1: the k selected scores are divided by their sum           */
+} moe_shape_t;
+
+#define MOE_MAX_EXPERTS 1024
+#define MOE_MAX_TOPK 64
+
+int moe_abi_version(void);
+const char* moe_last_error(void);
+
+/* Workspace sizes in bytes (host computation, no GPU call; 0 for invalid arguments).
+ * n_groups/n_rows as passed to the expert calls, shared = 1 for shared mode (offsets == NULL);
+ * `shape` supplies d, d_ff, dtype (and T, k, E for the dispatch). */
+size_t moe_dispatch_workspace_bytes(const moe_shape_t* shape);
+size_t moe_expert_fwd_workspace_bytes(const moe_shape_t* shape, int32_t n_groups, int32_t n_rows,
+                                      int32_t shared);
+size_t moe_expert_bwd_workspace_bytes(const moe_shape_t* shape, int32_t n_groups, int32_t n_rows,
+                                      int32_t shared);
+
+/*
+ * moe_route -- the gate of Eq. 3: g(x) and argtopk.
+ *   logits   [T, E] f32  router logits
+ *   topk_idx [T, k] i32  out: the k experts of each token, by descending logit; equal
+ *                        logits go to the lower expert index (selection is on the raw
+ *                        fp32 logits: softmax and sigmoid are increasing)
+ *   topk_w   [T, k] f32  out: g(x)_i of the selected experts (softmax over all E, or
+ *                        sigmoid), divided by their sum when shape->renorm
+ * NaN logits are a caller error (result unspecified, no fault).
+ */
+int moe_route(const moe_shape_t* shape, const float* logits, int32_t* topk_idx, float* topk_w,
+              void* stream);
+
+/*
+ * moe_dispatch -- group the T*k token-expert assignments by expert and copy the token rows
+ * into expert-contiguous order (the local-dispatch case of Algorithm 3: counts[e] is its
+ * token assignment T[e, d] for this device; no token is dropped).
+ *   X        [T, d]       tokens
+ *   topk_idx [T, k]       from moe_route
+ *   counts   [E]    i32   out: assignments per expert
+ *   offsets  [E+1]  i32   out: exclusive prefix sum of counts, offsets[E] = T*k
+ *   row_of   [T*k]  i32   out: row of assignment a = t*k + j in the grouped order; rows of
+ *                         one expert are in ascending a (stable counting sort)
+ *   src_of   [T*k]  i32   out: inverse of row_of
+ *   Xp       [T*k, d]     out: Xp[row_of[a], :] = X[a / k, :]
+ *   ws, ws_bytes          scratch of at least moe_dispatch_workspace_bytes(shape)
+ * Entries of topk_idx outside [0, E) are a caller error; they are ignored (no fault) and the
+ * outputs are then unspecified.
+ */
+int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                 int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* ws,
+                 size_t ws_bytes, void* stream);
+
+/*
+ * moe_expert_fwd -- the expert bodies of Eq. 3 as a grouped GEMM over variable row counts.
+ * Grouped mode (offsets != NULL): group e owns rows [offsets[e], offsets[e+1]) of Xin;
+ *   G = Xin_e Wg[e], U = Xin_e Wu[e], H = silu(G) * U, Yout_e = H Wd[e].
+ *   Groups without rows cost nothing (no tile, no weight read).
+ * Shared mode (offsets == NULL): each of the n_groups always-on experts runs on ALL n_rows
+ *   rows; G, U, H are [n_groups, n_rows, d_ff] and Yout is the sum over groups (Eq. 2).
+ *   n_groups  experts (shape->E in grouped mode; shape->E is not otherwise used here)
+ *   n_rows    rows of Xin (T*k in grouped mode, T in shared mode)
+ *   Xin  [n_rows, d]; Wg, Wu [n_groups, d, d_ff]; Wd [n_groups, d_ff, d]
+ *   G, U, H   out, [n_rows, d_ff] (shared: [n_groups, n_rows, d_ff]); kept for the backward pass
+ *   Yout [n_rows, d]  out
+ * shape->d_ff is the width of these experts (shared experts may use their own shape).
+ */
+int moe_expert_fwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* offsets, int32_t n_rows,
+                   const void* Xin, const void* Wg, const void* Wu, const void* Wd, void* G, void* U,
+                   void* H, void* Yout, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * moe_expert_bwd -- backward of moe_expert_fwd (chain rule on Eq. 1):
+ *   dH = dYin Wd^T;  s = sigmoid(G);  dU = dH * G * s;  dG = dH * U * s * (1 + G (1 - s));
+ *   dXin = dG Wg^T + dU Wu^T;  dWg = Xin^T dG;  dWu = Xin^T dU;  dWd = H^T dYin  (per group).
+ * The weight gradients are written COMPACTED to activated experts: active_ids lists, in
+ * ascending order, the groups that own at least one row (n_active of them; the remaining
+ * entries are -1) and slot i of dWg_c/dWu_c/dWd_c holds the gradient of group active_ids[i].
+ * Slots >= n_active are not written.  This is the per-GPU list of gradient chunks that the
+ * paper's SparseReduceScatter would send (one chunk per materialised expert, Eq. 4).
+ * Shared mode (offsets == NULL): every group is active, dXin is the sum over groups.
+ *   dYin [n_rows, d];  dXin [n_rows, d] out
+ *   active_ids [n_groups] i32 out;  n_active [1] i32 out (device)
+ *   dWg_c, dWu_c [n_groups, d, d_ff] out;  dWd_c [n_groups, d_ff, d] out
+ *   ws >= moe_expert_bwd_workspace_bytes(shape, n_groups, n_rows, offsets == NULL)
+ */
+int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* offsets, int32_t n_rows,
+                   const void* Xin, const void* Wg, const void* Wu, const void* Wd, const void* G,
+                   const void* U, const void* H, const void* dYin, void* dXin, int32_t* active_ids,
+                   int32_t* n_active, void* dWg_c, void* dWu_c, void* dWd_c, void* ws,
+                   size_t ws_bytes, void* stream);
+
+/*
+ * moe_combine -- the weighted sum of Eq. 3:
+ *   Y[t, :] = Yadd[t, :] + sum_j topk_w[t, j] * Yp[row_of[t*k + j], :]
+ * accumulated in fp32 and rounded once.  topk_w == NULL means unit weights (this is then the
+ * adjoint of the row copy of moe_dispatch, used for dX); Yadd == NULL means no added term
+ * (Yadd carries the shared experts' output).  Y may not alias Yp; Y may alias Yadd.
+ */
+int moe_combine(const moe_shape_t* shape, const void* Yp, const int32_t* row_of, const float* topk_w,
+                const void* Yadd, void* Y, void* stream);
+
+/*
+ * moe_combine_bwd -- backward of moe_combine with respect to Yp and the weights:
+ *   dYp[row_of[a], :] = topk_w[a] * dY[t, :];   dw[a] = <dY[t, :], Yp[row_of[a], :]>,  a = t*k + j.
+ *   dY [T, d];  Yp [T*k, d];  dYp [T*k, d] out;  dw [T, k] f32 out
+ */
+int moe_combine_bwd(const moe_shape_t* shape, const void* dY, const void* Yp, const int32_t* row_of,
+                    const float* topk_w, void* dYp, float* dw, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HIP_H */

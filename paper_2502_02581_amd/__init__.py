@@ -1,0 +1,13 @@
+"""MI355X-native hot path of one GPU's share of an MoE layer's training step.
+
+Thin Python binding over the C-ABI library libmoe_hip.so (declared in include/moe_hip.h).
+Every step of the path runs in hand-written HIP kernels; PyTorch only provides device
+memory and streams.  There is no CPU or PyTorch fallback: a missing library is an error.
+"""
+from .binding import (MoEShape, MoEHotPath, lib_path, load_library, moe_abi_version, moe_combine, moe_combine_bwd,
+                      moe_dispatch, moe_dispatch_workspace_bytes, moe_expert_bwd, moe_expert_bwd_workspace_bytes,
+                      moe_expert_fwd, moe_expert_fwd_workspace_bytes, moe_last_error, moe_route, MoEError)
+
+__all__ = ["MoEShape", "MoEHotPath", "MoEError", "lib_path", "load_library", "moe_abi_version", "moe_last_error",
+           "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine", "moe_combine_bwd",
+           "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes", "moe_expert_bwd_workspace_bytes"]

@@ -1,0 +1,253 @@
+"""ctypes binding of libmoe_hip.so: argument marshalling only, same names as the C ABI."""
+from __future__ import annotations
+
+import ctypes
+import dataclasses
+import os
+from typing import Dict, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libmoe_hip.so"
+_lib = None
+
+MOE_F32, MOE_BF16 = 0, 1
+MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
+EXPORTS = ["moe_abi_version", "moe_last_error", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
+           "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
+           "moe_combine", "moe_combine_bwd"]
+
+
+class MoEError(RuntimeError):
+    pass
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("T", "d", "E", "k", "d_ff", "dtype", "gate", "renorm")]
+
+
+@dataclasses.dataclass(frozen=True)
+class MoEShape:
+    T: int
+    d: int
+    E: int
+    k: int
+    d_ff: int
+    dtype: str = "bf16"      # "f32" | "bf16"
+    gate: str = "softmax"    # "softmax" | "sigmoid"
+    renorm: bool = True
+
+    def c(self) -> _CShape:
+        return _CShape(self.T, self.d, self.E, self.k, self.d_ff, MOE_F32 if self.dtype == "f32" else MOE_BF16,
+                       MOE_GATE_SOFTMAX if self.gate == "softmax" else MOE_GATE_SIGMOID, int(self.renorm))
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Loads the in-tree library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise MoEError(f"{path} is missing: build it with `python -m paper_2502_02581_amd.build` "
+                       "(hipcc, gfx950); this package has no CPU or PyTorch fallback")
+    lib = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    shp = ctypes.POINTER(_CShape)
+    lib.moe_abi_version.restype = ctypes.c_int
+    lib.moe_abi_version.argtypes = []
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_last_error.argtypes = []
+    lib.moe_dispatch_workspace_bytes.restype = sz
+    lib.moe_dispatch_workspace_bytes.argtypes = [shp]
+    for f in (lib.moe_expert_fwd_workspace_bytes, lib.moe_expert_bwd_workspace_bytes):
+        f.restype = sz
+        f.argtypes = [shp, i32, i32, i32]
+    lib.moe_route.restype = ctypes.c_int
+    lib.moe_route.argtypes = [shp, vp, vp, vp, vp]
+    lib.moe_dispatch.restype = ctypes.c_int
+    lib.moe_dispatch.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_expert_fwd.restype = ctypes.c_int
+    lib.moe_expert_fwd.argtypes = [shp, i32, vp, i32] + [vp] * 9 + [sz, vp]
+    lib.moe_expert_bwd.restype = ctypes.c_int
+    lib.moe_expert_bwd.argtypes = [shp, i32, vp, i32] + [vp] * 15 + [sz, vp]
+    lib.moe_combine.restype = ctypes.c_int
+    lib.moe_combine.argtypes = [shp, vp, vp, vp, vp, vp, vp]
+    lib.moe_combine_bwd.restype = ctypes.c_int
+    lib.moe_combine_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, what="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise MoEError(f"{what} must live on the GPU")
+    if not t.is_contiguous():
+        raise MoEError(f"{what} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise MoEError(f"{what} must be {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(rc: int, who: str):
+    if rc != 0:
+        raise MoEError(f"{who} failed ({rc}): {load_library().moe_last_error().decode()}")
+
+
+def moe_abi_version() -> int:
+    return load_library().moe_abi_version()
+
+
+def moe_last_error() -> str:
+    return load_library().moe_last_error().decode()
+
+
+def moe_dispatch_workspace_bytes(shape: MoEShape) -> int:
+    return load_library().moe_dispatch_workspace_bytes(ctypes.byref(shape.c()))
+
+
+def moe_expert_fwd_workspace_bytes(shape: MoEShape, n_groups: int, n_rows: int, shared: bool) -> int:
+    return load_library().moe_expert_fwd_workspace_bytes(ctypes.byref(shape.c()), n_groups, n_rows, int(shared))
+
+
+def moe_expert_bwd_workspace_bytes(shape: MoEShape, n_groups: int, n_rows: int, shared: bool) -> int:
+    return load_library().moe_expert_bwd_workspace_bytes(ctypes.byref(shape.c()), n_groups, n_rows, int(shared))
+
+
+def moe_route(shape: MoEShape, logits, topk_idx, topk_w, stream=None):
+    rc = load_library().moe_route(ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"),
+                                  _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"),
+                                  _stream(stream))
+    _check(rc, "moe_route")
+
+
+def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_dispatch(ctypes.byref(shape.c()), _ptr(X, dt, "X"), _ptr(topk_idx, torch.int32, "topk_idx"),
+                                     _ptr(counts, torch.int32, "counts"), _ptr(offsets, torch.int32, "offsets"),
+                                     _ptr(row_of, torch.int32, "row_of"), _ptr(src_of, torch.int32, "src_of"),
+                                     _ptr(Xp, dt, "Xp"), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(),
+                                     _stream(stream))
+    _check(rc, "moe_dispatch")
+
+
+def moe_expert_fwd(shape: MoEShape, n_groups, offsets, n_rows, Xin, Wg, Wu, Wd, G, U, H, Yout, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_expert_fwd(
+        ctypes.byref(shape.c()), n_groups, _ptr(offsets, torch.int32, "offsets"), n_rows, _ptr(Xin, dt, "Xin"),
+        _ptr(Wg, dt, "Wg"), _ptr(Wu, dt, "Wu"), _ptr(Wd, dt, "Wd"), _ptr(G, dt, "G"), _ptr(U, dt, "U"),
+        _ptr(H, dt, "H"), _ptr(Yout, dt, "Yout"), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(),
+        _stream(stream))
+    _check(rc, "moe_expert_fwd")
+
+
+def moe_expert_bwd(shape: MoEShape, n_groups, offsets, n_rows, Xin, Wg, Wu, Wd, G, U, H, dYin, dXin, active_ids,
+                   n_active, dWg_c, dWu_c, dWd_c, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_expert_bwd(
+        ctypes.byref(shape.c()), n_groups, _ptr(offsets, torch.int32, "offsets"), n_rows, _ptr(Xin, dt, "Xin"),
+        _ptr(Wg, dt, "Wg"), _ptr(Wu, dt, "Wu"), _ptr(Wd, dt, "Wd"), _ptr(G, dt, "G"), _ptr(U, dt, "U"),
+        _ptr(H, dt, "H"), _ptr(dYin, dt, "dYin"), _ptr(dXin, dt, "dXin"), _ptr(active_ids, torch.int32, "active_ids"),
+        _ptr(n_active, torch.int32, "n_active"), _ptr(dWg_c, dt, "dWg_c"), _ptr(dWu_c, dt, "dWu_c"),
+        _ptr(dWd_c, dt, "dWd_c"), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_expert_bwd")
+
+
+def moe_combine(shape: MoEShape, Yp, row_of, topk_w, Yadd, Y, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_combine(ctypes.byref(shape.c()), _ptr(Yp, dt, "Yp"), _ptr(row_of, torch.int32, "row_of"),
+                                    _ptr(topk_w, torch.float32, "topk_w"), _ptr(Yadd, dt, "Yadd"), _ptr(Y, dt, "Y"),
+                                    _stream(stream))
+    _check(rc, "moe_combine")
+
+
+def moe_combine_bwd(shape: MoEShape, dY, Yp, row_of, topk_w, dYp, dw, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_combine_bwd(ctypes.byref(shape.c()), _ptr(dY, dt, "dY"), _ptr(Yp, dt, "Yp"),
+                                        _ptr(row_of, torch.int32, "row_of"), _ptr(topk_w, torch.float32, "topk_w"),
+                                        _ptr(dYp, dt, "dYp"), _ptr(dw, torch.float32, "dw"), _stream(stream))
+    _check(rc, "moe_combine_bwd")
+
+
+class MoEHotPath:
+    """Owns the device buffers of one layer and chains the C calls of a training step.
+
+    forward():  moe_route -> moe_dispatch -> moe_expert_fwd (routed, then shared) -> moe_combine
+    backward(): moe_combine_bwd -> moe_expert_bwd (routed, then shared) -> moe_combine (unit weights)
+    No arithmetic happens here; tensors are only allocated and handed to the library.
+    """
+
+    def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0"):
+        self.shape, self.S, self.Fs, self.device = shape, n_shared, d_ff_shared, torch.device(device)
+        s, dt, dev = shape, shape.torch_dtype, self.device
+        A = s.T * s.k
+        i32 = dict(dtype=torch.int32, device=dev)
+        f = dict(dtype=dt, device=dev)
+        self.b: Dict[str, torch.Tensor] = {
+            "topk_idx": torch.empty(s.T, s.k, **i32), "topk_w": torch.empty(s.T, s.k, dtype=torch.float32, device=dev),
+            "counts": torch.empty(s.E, **i32), "offsets": torch.empty(s.E + 1, **i32),
+            "row_of": torch.empty(A, **i32), "src_of": torch.empty(A, **i32),
+            "Xp": torch.empty(A, s.d, **f), "G": torch.empty(A, s.d_ff, **f), "U": torch.empty(A, s.d_ff, **f),
+            "H": torch.empty(A, s.d_ff, **f), "Yp": torch.empty(A, s.d, **f), "Y": torch.empty(s.T, s.d, **f),
+            "dYp": torch.empty(A, s.d, **f), "dw": torch.empty(s.T, s.k, dtype=torch.float32, device=dev),
+            "dXp": torch.empty(A, s.d, **f), "dX": torch.empty(s.T, s.d, **f),
+            "active_ids": torch.empty(s.E, **i32), "n_active": torch.empty(1, **i32),
+            "dWg_c": torch.empty(s.E, s.d, s.d_ff, **f), "dWu_c": torch.empty(s.E, s.d, s.d_ff, **f),
+            "dWd_c": torch.empty(s.E, s.d_ff, s.d, **f),
+        }
+        ws = max(moe_dispatch_workspace_bytes(s), moe_expert_fwd_workspace_bytes(s, s.E, A, False),
+                 moe_expert_bwd_workspace_bytes(s, s.E, A, False))
+        if n_shared:
+            self.sshape = dataclasses.replace(s, d_ff=d_ff_shared)
+            S, Fs = n_shared, d_ff_shared
+            self.b.update({
+                "Gs": torch.empty(S, s.T, Fs, **f), "Us": torch.empty(S, s.T, Fs, **f), "Hs": torch.empty(S, s.T, Fs, **f),
+                "Ysh": torch.empty(s.T, s.d, **f), "dXsh": torch.empty(s.T, s.d, **f),
+                "s_active_ids": torch.empty(S, **i32), "s_n_active": torch.empty(1, **i32),
+                "dWsg": torch.empty(S, s.d, Fs, **f), "dWsu": torch.empty(S, s.d, Fs, **f),
+                "dWsd": torch.empty(S, Fs, s.d, **f),
+            })
+            ws = max(ws, moe_expert_fwd_workspace_bytes(self.sshape, S, s.T, True),
+                     moe_expert_bwd_workspace_bytes(self.sshape, S, s.T, True))
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+
+    def forward(self, logits, X, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, stream=None):
+        s, b = self.shape, self.b
+        A = s.T * s.k
+        moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
+        moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
+        moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
+        if self.S:
+            moe_expert_fwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], b["Ysh"],
+                           self.ws, stream)
+        moe_combine(s, b["Yp"], b["row_of"], b["topk_w"], b["Ysh"] if self.S else None, b["Y"], stream)
+        return b["Y"]
+
+    def backward(self, dY, X, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, stream=None):
+        s, b = self.shape, self.b
+        A = s.T * s.k
+        moe_combine_bwd(s, dY, b["Yp"], b["row_of"], b["topk_w"], b["dYp"], b["dw"], stream)
+        moe_expert_bwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["dYp"], b["dXp"],
+                       b["active_ids"], b["n_active"], b["dWg_c"], b["dWu_c"], b["dWd_c"], self.ws, stream)
+        if self.S:
+            moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
+                           b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws, stream)
+        moe_combine(s, b["dXp"], b["row_of"], None, b["dXsh"] if self.S else None, b["dX"], stream)
+        return b["dX"]

@@ -1,0 +1,169 @@
+// moe_dispatch: stable counting sort of the T*k assignments by expert, then the row copy.
+//
+//   1. dispatch_count  one wavefront per chunk of kChunk assignments: LDS histogram over experts
+//                      (LDS atomics are used for the COUNTS only, so the result does not depend
+//                      on their order), written to ws as hist[chunk][e].
+//   2. dispatch_scan   one block: exclusive scan over chunks per expert (in place), counts,
+//                      and the exclusive scan over experts (offsets).
+//   3. dispatch_rank   one wavefront per chunk: walks its chunk in assignment order; the rank of
+//                      an assignment among equal experts inside a 64-wide step comes from
+//                      ballots in lane order, so row_of is the same on every run (stable sort).
+//   4. dispatch_rows   one block per token: reads the token row once, writes it to its k rows.
+#include "moe_common.h"
+
+namespace moe {
+
+constexpr int kChunk = 256;  // assignments per wavefront in steps 1 and 3
+
+__global__ __launch_bounds__(64) void dispatch_count(const int32_t* __restrict__ topk_idx, int A, int E,
+                                                     int32_t* __restrict__ hist) {
+  __shared__ int32_t cnt[MOE_MAX_EXPERTS];
+  const int lane = threadIdx.x;
+  const int chunk = blockIdx.x;
+  for (int e = lane; e < E; e += 64) cnt[e] = 0;
+  __syncthreads();
+  const int a0 = chunk * kChunk;
+  for (int s = 0; s < kChunk; s += 64) {
+    int a = a0 + s + lane;
+    if (a < A) {
+      int e = topk_idx[a];
+      if (e >= 0 && e < E) atomicAdd(&cnt[e], 1);
+    }
+  }
+  __syncthreads();
+  for (int e = lane; e < E; e += 64) hist[(size_t)chunk * E + e] = cnt[e];
+}
+
+__global__ __launch_bounds__(1024) void dispatch_scan(int32_t* __restrict__ hist, int n_chunks, int E,
+                                                      int32_t* __restrict__ counts,
+                                                      int32_t* __restrict__ offsets) {
+  __shared__ int32_t sc[MOE_MAX_EXPERTS];
+  const int e = threadIdx.x;
+  int run = 0;
+  if (e < E) {
+    for (int c = 0; c < n_chunks; c++) {
+      int v = hist[(size_t)c * E + e];
+      hist[(size_t)c * E + e] = run;
+      run += v;
+    }
+    counts[e] = run;
+  }
+  sc[e] = e < E ? run : 0;
+  __syncthreads();
+  // inclusive Hillis-Steele scan over the (at most 1024) experts
+  for (int step = 1; step < MOE_MAX_EXPERTS; step <<= 1) {
+    int add = e >= step ? sc[e - step] : 0;
+    __syncthreads();
+    sc[e] += add;
+    __syncthreads();
+  }
+  if (e < E) offsets[e + 1] = sc[e];
+  if (e == 0) offsets[0] = 0;
+}
+
+__global__ __launch_bounds__(64) void dispatch_rank(const int32_t* __restrict__ topk_idx, int A, int E,
+                                                    const int32_t* __restrict__ hist,
+                                                    const int32_t* __restrict__ offsets,
+                                                    int32_t* __restrict__ row_of,
+                                                    int32_t* __restrict__ src_of) {
+  __shared__ int32_t nxt[MOE_MAX_EXPERTS];
+  const int lane = threadIdx.x;
+  const int chunk = blockIdx.x;
+  for (int e = lane; e < E; e += 64) nxt[e] = offsets[e] + hist[(size_t)chunk * E + e];
+  __syncthreads();
+  const int a0 = chunk * kChunk;
+  const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  for (int s = 0; s < kChunk; s += 64) {
+    const int a = a0 + s + lane;
+    int e = -1;
+    if (a < A) {
+      e = topk_idx[a];
+      if (e < 0 || e >= E) e = -1;
+    }
+    const bool valid = e >= 0;
+    uint64_t todo = __ballot(valid);
+    int rank = 0, group = 0;
+    bool last = false;
+    while (todo) {
+      int leader = __ffsll((unsigned long long)todo) - 1;
+      int le = __shfl(e, leader, kWave);
+      uint64_t same = __ballot(valid && e == le);
+      if (valid && e == le) {
+        rank = __popcll(same & lt_mask);
+        group = __popcll(same);
+        last = (same >> lane) == 1ull;  // highest lane of the group
+      }
+      todo &= ~same;
+    }
+    int r = 0;
+    if (valid) r = nxt[e] + rank;
+    __syncthreads();
+    if (valid && last) nxt[e] += group;
+    __syncthreads();
+    if (valid) {
+      row_of[a] = r;
+      src_of[r] = a;
+    }
+  }
+}
+
+// Xp[row_of[t*k+j], :] = X[t, :], 16 bytes per lane per access
+__global__ __launch_bounds__(256) void dispatch_rows(const uint4* __restrict__ X,
+                                                     const int32_t* __restrict__ row_of, int k,
+                                                     int vec_per_row, uint4* __restrict__ Xp) {
+  const int t = blockIdx.x;
+  const uint4* src = X + (size_t)t * vec_per_row;
+  for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+    uint4 v = src[c];
+    for (int j = 0; j < k; j++) {
+      int r = row_of[(size_t)t * k + j];
+      Xp[(size_t)r * vec_per_row + c] = v;
+    }
+  }
+}
+
+}  // namespace moe
+
+extern "C" size_t moe_dispatch_workspace_bytes(const moe_shape_t* shape) {
+  using namespace moe;
+  if (!shape || shape->E < 1 || shape->T < 0 || shape->k < 1) return 0;
+  size_t A = (size_t)shape->T * shape->k;
+  size_t n_chunks = (A + kChunk - 1) / kChunk;
+  return align_up((n_chunks > 0 ? n_chunks : 1) * (size_t)shape->E * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                            int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* ws,
+                            size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_dispatch");
+  if (rc) return rc;
+  if (!topk_idx || !counts || !offsets || !row_of || !src_of || !ws || (shape->T > 0 && (!X || !Xp))) {
+    set_error("moe_dispatch: null pointer");
+    return MOE_EINVAL;
+  }
+  if (!aligned16(X) || !aligned16(Xp) || !aligned16(ws)) {
+    set_error("moe_dispatch: X, Xp and ws must be 16-byte aligned");
+    return MOE_EINVAL;
+  }
+  if (ws_bytes < moe_dispatch_workspace_bytes(shape)) {
+    set_error("moe_dispatch: workspace of %zu bytes, need %zu", ws_bytes, moe_dispatch_workspace_bytes(shape));
+    return MOE_EWS;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int A = shape->T * shape->k;
+  const int n_chunks = (A + kChunk - 1) / kChunk;
+  int32_t* hist = (int32_t*)ws;
+  if (n_chunks > 0) {
+    hipLaunchKernelGGL(dispatch_count, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist);
+  }
+  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(1024), 0, st, hist, n_chunks, shape->E, counts, offsets);
+  if (n_chunks > 0) {
+    hipLaunchKernelGGL(dispatch_rank, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist, offsets,
+                       row_of, src_of);
+    const int vec_per_row = (int)((size_t)shape->d * elem_size(shape->dtype) / 16);
+    hipLaunchKernelGGL(dispatch_rows, dim3(shape->T), dim3(256), 0, st, (const uint4*)X, row_of, shape->k,
+                       vec_per_row, (uint4*)Xp);
+  }
+  return launch_status("moe_dispatch");
+}

@@ -1,0 +1,450 @@
+// moe_expert_fwd / moe_expert_bwd: the expert bodies of Eq. 3 (SwiGLU reading of Eq. 1) as
+// grouped GEMMs over variable per-expert row counts, and their backward pass.
+//
+// Forward   F4: [G | U] = Xin_e [Wg_e | Wu_e],  H = silu(G) * U   (dual GEMM, fused epilogue)
+//           F5: Yout_e = H_e Wd_e
+// Backward  B2a: dH = dYin_e Wd_e^T, epilogue -> dG, dU           (reads the saved G, U)
+//           B2b: dXin_e = dG_e Wg_e^T + dU_e Wu_e^T               (two K segments)
+//           B3 : dWd_e = H_e^T dYin_e;  [dWg_e | dWu_e] = Xin_e^T [dG_e | dU_e]
+// A device-built plan turns the row offsets into a list of row tiles (largest group first,
+// groups without rows contribute nothing) so that no host synchronisation is needed.
+#include "gemm_cores.h"
+#include "gemm_plan.h"
+
+namespace moe {
+
+// ------------------------------------------------------------------------------------ plan
+__device__ __forceinline__ void block_scan_inclusive(int32_t* sc, int e) {
+  for (int step = 1; step < 1024; step <<= 1) {
+    int add = e >= step ? sc[e - step] : 0;
+    __syncthreads();
+    sc[e] += add;
+    __syncthreads();
+  }
+}
+
+// One block of 1024 threads; thread e owns group e.
+__global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ offsets, int n_groups,
+                                                    int n_rows, int BM, Plan pl, int32_t* active_ids,
+                                                    int32_t* n_active) {
+  __shared__ int32_t cnt[1024], sc[1024], ord[1024], st_[1024];
+  const int e = threadIdx.x;
+  int c = 0, st = 0;
+  if (e < n_groups) {
+    if (offsets) {
+      st = offsets[e];
+      c = offsets[e + 1] - st;
+      if (c < 0) c = 0;
+    } else {
+      c = n_rows;
+    }
+  }
+  cnt[e] = e < n_groups ? c : -1;
+  st_[e] = st;
+  sc[e] = (e < n_groups && c > 0) ? 1 : 0;
+  __syncthreads();
+  if (e < n_groups) {
+    int rank = 0;
+    for (int o = 0; o < n_groups; o++) {
+      int co = cnt[o];
+      rank += (co > c) || (co == c && o < e);
+    }
+    ord[rank] = e;
+    pl.order[rank] = e;
+    pl.counts[e] = c;
+    pl.starts[e] = st;
+  }
+  block_scan_inclusive(sc, e);
+  const int total_active = sc[1023];
+  if (e < n_groups) {
+    const int slot = c > 0 ? sc[e] - 1 : -1;
+    pl.slot_of[e] = slot;
+    if (active_ids) {
+      if (slot >= 0) active_ids[slot] = e;
+      if (e >= total_active) active_ids[e] = -1;
+    }
+  }
+  if (e == 0 && n_active) *n_active = total_active;
+  __syncthreads();
+  // row tiles, groups in descending size
+  const int g = e < n_groups ? ord[e] : 0;
+  const int cg = e < n_groups ? cnt[g] : 0;
+  const int nt = (cg + BM - 1) / BM;
+  sc[e] = nt;
+  __syncthreads();
+  block_scan_inclusive(sc, e);
+  const int base = sc[e] - nt;
+  for (int i = 0; i < nt; i++) {
+    RowTile t;
+    t.group = g;
+    t.row0_in = st_[g] + i * BM;
+    t.rows = min(BM, cg - i * BM);
+    t.row0_out = offsets ? t.row0_in : g * n_rows + i * BM;
+    pl.tiles[base + i] = t;
+  }
+  if (e == 1023) *pl.n_tiles = sc[1023];
+}
+
+// ------------------------------------------------------------------------------- epilogues
+template <typename T> __device__ __forceinline__ void store4(T* p, const float (&v)[4]);
+template <> __device__ __forceinline__ void store4<float>(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const float (&v)[4]) {
+  uint2 w;
+  w.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+  w.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  *reinterpret_cast<uint2*>(p) = w;
+}
+template <typename T> __device__ __forceinline__ void load4(const T* p, float (&v)[4]);
+template <> __device__ __forceinline__ void load4<float>(const float* p, float (&v)[4]) {
+  float4 f = *reinterpret_cast<const float4*>(p);
+  v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  uint2 w = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(w.x << 16);
+  v[1] = __uint_as_float(w.x & 0xffff0000u);
+  v[2] = __uint_as_float(w.y << 16);
+  v[3] = __uint_as_float(w.y & 0xffff0000u);
+}
+
+enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2 };
+
+__device__ __forceinline__ float sigmoidf_(float z) { return 1.f / (1.f + expf(-z)); }
+
+// --------------------------------------------------------------------- row-tiled GEMM kernel
+template <class Core, int NB, int EPI, bool B_KC>
+__global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
+  typedef typename Core::T T;
+  extern __shared__ __align__(16) char smem[];
+  constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
+  const int ntn = (p.N + BN - 1) / BN;
+  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  RowTile t;
+  if (p.tiles) {
+    if (mt >= *p.n_tiles) return;
+    t = p.tiles[mt];
+  } else {
+    t.group = 0;
+    t.row0_in = mt * BM;
+    if (t.row0_in >= p.n_rows) return;
+    t.rows = min(BM, p.n_rows - t.row0_in);
+    t.row0_out = t.row0_in;
+  }
+  const int n0 = nt * BN;
+  const int n_valid = min(BN, p.N - n0);
+  const int a_row0 = p.a_rows_out ? t.row0_out : t.row0_in;
+  const int nk = (p.K + BK - 1) / BK;
+  const int per_pair = p.n_segs * nk;
+  auto src = [&](int it) {
+    IterSrc<T, NB> s;
+    const int pair = it / per_pair, rem = it % per_pair;
+    const int seg = rem / nk, k0 = (rem % nk) * BK;
+    s.a = (const T*)p.A[pair] + seg * p.a_seg + (int64_t)a_row0 * p.lda + k0;
+    const int64_t boff = (int64_t)t.group * p.b_group + seg * p.b_seg + (B_KC ? (int64_t)n0 * p.ldb + k0 : (int64_t)k0 * p.ldb + n0);
+    s.b[0] = (const T*)p.B[pair] + boff;
+    if (NB == 2) s.b[NB - 1] = (const T*)p.Bdual + boff;
+    s.k_left = p.K - k0;
+    return s;
+  };
+  const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
+  auto epi = [&](int m, int n, const float (&v)[NB][4]) {
+    if (m >= t.rows || n >= n_valid) return;
+    const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
+    if (EPI == EPI_STORE) {
+      store4<T>((T*)p.out[0] + off, v[0]);
+    } else if (EPI == EPI_SWIGLU_FWD) {
+      float h[4];
+#pragma unroll
+      for (int q = 0; q < 4; q++) h[q] = v[0][q] * sigmoidf_(v[0][q]) * v[NB - 1][q];
+      store4<T>((T*)p.out[0] + off, v[0]);
+      store4<T>((T*)p.out[1] + off, v[NB - 1]);
+      store4<T>((T*)p.out[2] + off, h);
+    } else {
+      float g[4], u[4], dg[4], du[4];
+      load4<T>((const T*)p.in[0] + off, g);
+      load4<T>((const T*)p.in[1] + off, u);
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const float s = sigmoidf_(g[q]);
+        du[q] = v[0][q] * g[q] * s;
+        dg[q] = v[0][q] * u[q] * s * (1.f + g[q] * (1.f - s));
+      }
+      store4<T>((T*)p.out[0] + off, dg);
+      store4<T>((T*)p.out[1] + off, du);
+    }
+  };
+  Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, t.rows, n_valid, epi);
+}
+
+// ------------------------------------------------------------------- weight-gradient kernel
+template <class Core, int NB>
+__global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
+  typedef typename Core::T T;
+  extern __shared__ __align__(16) char smem[];
+  constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
+  const int g = p.order ? p.order[blockIdx.y] : blockIdx.y;
+  const int K = p.counts ? p.counts[g] : p.n_rows;
+  if (K <= 0) return;
+  const int start = p.starts ? p.starts[g] : 0;
+  const int slot = p.slot_of ? p.slot_of[g] : g;
+  const int ntn = (p.N + BN - 1) / BN;
+  const int m0 = (blockIdx.x / ntn) * BM, n0 = (blockIdx.x % ntn) * BN;
+  const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
+  const int a_row0 = start + (p.a_per_group ? g * p.n_rows : 0);
+  const int b_row0 = start + (p.b_per_group ? g * p.n_rows : 0);
+  auto src = [&](int it) {
+    IterSrc<T, NB> s;
+    const int k0 = it * BK;
+    s.a = (const T*)p.A + (int64_t)(a_row0 + k0) * p.lda + m0;
+    s.b[0] = (const T*)p.B[0] + (int64_t)(b_row0 + k0) * p.ldb + n0;
+    if (NB == 2) s.b[NB - 1] = (const T*)p.B[1] + (int64_t)(b_row0 + k0) * p.ldb + n0;
+    s.k_left = K - k0;
+    return s;
+  };
+  auto epi = [&](int m, int n, const float (&v)[NB][4]) {
+    if (m >= m_valid || n >= n_valid) return;
+    const int64_t off = (int64_t)slot * p.c_slot + (int64_t)(m0 + m) * p.N + n0 + n;
+    store4<T>((T*)p.C[0] + off, v[0]);
+    if (NB == 2) store4<T>((T*)p.C[1] + off, v[NB - 1]);
+  };
+  Core::run(smem, (K + BK - 1) / BK, src, p.lda, p.ldb, m_valid, n_valid, epi);
+}
+
+// ------------------------------------------------------------------------------ host side
+template <int DT> struct Cores;
+template <> struct Cores<MOE_F32> {
+  static constexpr int BM = 64, BN = 64;
+  template <int NB, bool A_KC, bool B_KC> using core = F32Core<NB, A_KC, B_KC>;
+};
+template <> struct Cores<MOE_BF16> {
+  static constexpr int BM = 128, BN = 128;
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaCore<128, 128, NB, A_KC, B_KC>;
+};
+
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+static int max_row_tiles(int n_groups, int n_rows, bool shared, int BM) {
+  return shared ? n_groups * ceil_div(n_rows, BM) : ceil_div(n_rows, BM) + n_groups;
+}
+
+template <class Core, int NB, int EPI, bool B_KC>
+static void launch_row(const RowGemm& p, int max_tiles, hipStream_t st) {
+  const int ntn = ceil_div(p.N, Core::BN);
+  const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, Core::BM);
+  if (n_mt == 0 || ntn == 0) return;
+  auto kern = row_gemm_kernel<Core, NB, EPI, B_KC>;
+  static bool attr_done = false;
+  if (!attr_done && Core::LDS_BYTES > 48 * 1024) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)(n_mt * ntn)), dim3(256), Core::LDS_BYTES, st, p);
+}
+
+template <class Core, int NB>
+static void launch_w(const WGemm& p, int n_groups, hipStream_t st) {
+  const int tiles = ceil_div(p.M, Core::BM) * ceil_div(p.N, Core::BN);
+  if (tiles == 0 || n_groups == 0) return;
+  auto kern = w_gemm_kernel<Core, NB>;
+  static bool attr_done = false;
+  if (!attr_done && Core::LDS_BYTES > 48 * 1024) {
+    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups), dim3(256), Core::LDS_BYTES, st, p);
+}
+
+struct FwdArgs {
+  int d, F, n_groups, n_rows;
+  const int32_t* offsets;
+  const void *Xin, *Wg, *Wu, *Wd;
+  void *G, *U, *H, *Yout;
+  void* ws;
+};
+
+template <int DT>
+static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
+  typedef Cores<DT> C;
+  const bool shared = a.offsets == nullptr;
+  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
+  Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+                     (int32_t*)nullptr, (int32_t*)nullptr);
+  // F4: dual GEMM with the SwiGLU epilogue
+  RowGemm p = {};
+  p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
+  p.N = a.F; p.K = a.d; p.n_pairs = 1; p.n_segs = 1;
+  p.A[0] = a.Xin; p.lda = a.d; p.a_seg = 0; p.a_rows_out = 0;
+  p.B[0] = a.Wg; p.Bdual = a.Wu; p.ldb = a.F; p.b_group = (int64_t)a.d * a.F; p.b_seg = 0;
+  p.out[0] = a.G; p.out[1] = a.U; p.out[2] = a.H; p.ldc = a.F; p.c_rows_out = 1;
+  launch_row<typename C::template core<2, true, false>, 2, EPI_SWIGLU_FWD, false>(p, max_tiles, st);
+  // F5: Yout = H Wd (shared mode: summed over groups through K segments)
+  RowGemm q = {};
+  q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 1;
+  q.A[0] = a.H; q.lda = a.F; q.a_rows_out = 1;
+  q.B[0] = a.Wd; q.ldb = a.d;
+  q.out[0] = a.Yout; q.ldc = a.d; q.c_rows_out = 0;
+  if (shared) {
+    q.tiles = nullptr; q.n_segs = a.n_groups; q.a_seg = (int64_t)a.n_rows * a.F; q.b_seg = (int64_t)a.F * a.d;
+    q.b_group = 0;
+  } else {
+    q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.F * a.d;
+  }
+  launch_row<typename C::template core<1, true, false>, 1, EPI_STORE, false>(q, max_tiles, st);
+}
+
+struct BwdArgs {
+  int d, F, n_groups, n_rows;
+  const int32_t* offsets;
+  const void *Xin, *Wg, *Wu, *Wd, *G, *U, *H, *dYin;
+  void* dXin;
+  int32_t *active_ids, *n_active;
+  void *dWg, *dWu, *dWd;
+  void* ws;
+  size_t plan_sz;
+};
+
+template <int DT>
+static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
+  typedef Cores<DT> C;
+  const bool shared = a.offsets == nullptr;
+  const size_t es = elem_size(DT);
+  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
+  Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
+  const size_t act_rows = (size_t)(shared ? a.n_groups : 1) * a.n_rows;
+  char* dG = (char*)a.ws + a.plan_sz;
+  char* dU = dG + align_up(act_rows * a.F * es, 256);
+  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+                     a.active_ids, a.n_active);
+  // B2a: dH = dYin Wd^T, epilogue turns it into dG, dU
+  RowGemm p = {};
+  p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
+  p.N = a.F; p.K = a.d; p.n_pairs = 1; p.n_segs = 1;
+  p.A[0] = a.dYin; p.lda = a.d; p.a_rows_out = 0;
+  p.B[0] = a.Wd; p.ldb = a.d; p.b_group = (int64_t)a.F * a.d;
+  p.in[0] = a.G; p.in[1] = a.U; p.out[0] = dG; p.out[1] = dU; p.ldc = a.F; p.c_rows_out = 1;
+  launch_row<typename C::template core<1, true, true>, 1, EPI_SWIGLU_BWD, true>(p, max_tiles, st);
+  // B2b: dXin = dG Wg^T + dU Wu^T
+  RowGemm q = {};
+  q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 2;
+  q.A[0] = dG; q.A[1] = dU; q.lda = a.F; q.a_rows_out = 1;
+  q.B[0] = a.Wg; q.B[1] = a.Wu; q.ldb = a.F;
+  q.out[0] = a.dXin; q.ldc = a.d; q.c_rows_out = 0;
+  if (shared) {
+    q.tiles = nullptr; q.n_segs = a.n_groups; q.a_seg = (int64_t)a.n_rows * a.F; q.b_seg = (int64_t)a.d * a.F;
+    q.b_group = 0;
+  } else {
+    q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.d * a.F;
+  }
+  launch_row<typename C::template core<1, true, true>, 1, EPI_STORE, true>(q, max_tiles, st);
+  // B3: weight gradients, compacted to active groups, largest group first
+  WGemm w = {};
+  w.order = pl.order; w.slot_of = pl.slot_of; w.counts = pl.counts; w.starts = pl.starts; w.n_rows = a.n_rows;
+  w.M = a.F; w.N = a.d;
+  w.A = a.H; w.lda = a.F; w.a_per_group = shared;
+  w.B[0] = a.dYin; w.ldb = a.d; w.b_per_group = 0;
+  w.C[0] = a.dWd; w.c_slot = (int64_t)a.F * a.d;
+  launch_w<typename C::template core<1, false, false>, 1>(w, a.n_groups, st);
+  WGemm v = {};
+  v.order = pl.order; v.slot_of = pl.slot_of; v.counts = pl.counts; v.starts = pl.starts; v.n_rows = a.n_rows;
+  v.M = a.d; v.N = a.F;
+  v.A = a.Xin; v.lda = a.d; v.a_per_group = 0;
+  v.B[0] = dG; v.B[1] = dU; v.ldb = a.F; v.b_per_group = shared;
+  v.C[0] = a.dWg; v.C[1] = a.dWu; v.c_slot = (int64_t)a.d * a.F;
+  launch_w<typename C::template core<2, false, false>, 2>(v, a.n_groups, st);
+}
+
+static size_t plan_size_for(const moe_shape_t* s, int n_groups, int n_rows, bool shared) {
+  const int BM = s->dtype == MOE_F32 ? Cores<MOE_F32>::BM : Cores<MOE_BF16>::BM;
+  return align_up(plan_bytes(n_groups, max_row_tiles(n_groups, n_rows, shared, BM) + 1), 256);
+}
+
+static int check_expert_args(const moe_shape_t* s, int n_groups, int n_rows, const char* who) {
+  int rc = check_shape(s, who);
+  if (rc) return rc;
+  if (n_groups < 1 || n_groups > MOE_MAX_EXPERTS || n_rows < 0 || (int64_t)n_groups * n_rows >= (int64_t)1 << 31) {
+    set_error("%s: bad n_groups=%d n_rows=%d", who, n_groups, n_rows);
+    return MOE_EINVAL;
+  }
+  return MOE_OK;
+}
+
+}  // namespace moe
+
+extern "C" size_t moe_expert_fwd_workspace_bytes(const moe_shape_t* shape, int32_t n_groups, int32_t n_rows,
+                                                 int32_t shared) {
+  using namespace moe;
+  if (!shape || n_groups < 1 || n_rows < 0) return 0;
+  return plan_size_for(shape, n_groups, n_rows, shared != 0);
+}
+
+// plan + dG + dU ([n_rows, d_ff] each; shared mode keeps them per group)
+extern "C" size_t moe_expert_bwd_workspace_bytes(const moe_shape_t* shape, int32_t n_groups, int32_t n_rows,
+                                                 int32_t shared) {
+  using namespace moe;
+  if (!shape || n_groups < 1 || n_rows < 0) return 0;
+  const size_t rows = (size_t)(shared ? n_groups : 1) * (size_t)n_rows;
+  return plan_size_for(shape, n_groups, n_rows, shared != 0) +
+         2 * align_up(rows * shape->d_ff * elem_size(shape->dtype), 256);
+}
+
+extern "C" int moe_expert_fwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* offsets, int32_t n_rows,
+                              const void* Xin, const void* Wg, const void* Wu, const void* Wd, void* G, void* U,
+                              void* H, void* Yout, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_expert_args(shape, n_groups, n_rows, "moe_expert_fwd");
+  if (rc) return rc;
+  if (!Wg || !Wu || !Wd || !ws || (n_rows > 0 && (!Xin || !G || !U || !H || !Yout))) {
+    set_error("moe_expert_fwd: null pointer");
+    return MOE_EINVAL;
+  }
+  const void* ptrs[] = {Xin, Wg, Wu, Wd, G, U, H, Yout, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) {
+      set_error("moe_expert_fwd: every tensor must be 16-byte aligned");
+      return MOE_EINVAL;
+    }
+  if (ws_bytes < moe_expert_fwd_workspace_bytes(shape, n_groups, n_rows, offsets == nullptr)) {
+    set_error("moe_expert_fwd: workspace of %zu bytes, need %zu", ws_bytes,
+              moe_expert_fwd_workspace_bytes(shape, n_groups, n_rows, offsets == nullptr));
+    return MOE_EWS;
+  }
+  if (n_rows == 0) return MOE_OK;
+  FwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xin, Wg, Wu, Wd, G, U, H, Yout, ws};
+  if (shape->dtype == MOE_F32) expert_fwd_impl<MOE_F32>(a, (hipStream_t)stream);
+  else expert_fwd_impl<MOE_BF16>(a, (hipStream_t)stream);
+  return launch_status("moe_expert_fwd");
+}
+
+extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* offsets, int32_t n_rows,
+                              const void* Xin, const void* Wg, const void* Wu, const void* Wd, const void* G,
+                              const void* U, const void* H, const void* dYin, void* dXin, int32_t* active_ids,
+                              int32_t* n_active, void* dWg_c, void* dWu_c, void* dWd_c, void* ws,
+                              size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_expert_args(shape, n_groups, n_rows, "moe_expert_bwd");
+  if (rc) return rc;
+  if (!Wg || !Wu || !Wd || !ws || !active_ids || !n_active || !dWg_c || !dWu_c || !dWd_c ||
+      (n_rows > 0 && (!Xin || !G || !U || !H || !dYin || !dXin))) {
+    set_error("moe_expert_bwd: null pointer");
+    return MOE_EINVAL;
+  }
+  const void* ptrs[] = {Xin, Wg, Wu, Wd, G, U, H, dYin, dXin, dWg_c, dWu_c, dWd_c, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) {
+      set_error("moe_expert_bwd: every tensor must be 16-byte aligned");
+      return MOE_EINVAL;
+    }
+  const size_t need = moe_expert_bwd_workspace_bytes(shape, n_groups, n_rows, offsets == nullptr);
+  if (ws_bytes < need) {
+    set_error("moe_expert_bwd: workspace of %zu bytes, need %zu", ws_bytes, need);
+    return MOE_EWS;
+  }
+  BwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xin, Wg, Wu, Wd, G, U, H, dYin, dXin,
+               active_ids, n_active, dWg_c, dWu_c, dWd_c, ws, plan_size_for(shape, n_groups, n_rows, offsets == nullptr)};
+  if (shape->dtype == MOE_F32) expert_bwd_impl<MOE_F32>(a, (hipStream_t)stream);
+  else expert_bwd_impl<MOE_BF16>(a, (hipStream_t)stream);
+  return launch_status("moe_expert_bwd");
+}

@@ -1,0 +1,86 @@
+// Tile plan and argument blocks of the grouped GEMMs (device side).
+#pragma once
+
+#include "moe_common.h"
+
+namespace moe {
+
+// One row tile of a grouped GEMM whose C rows are token rows.
+struct RowTile {
+  int32_t group;     // expert that owns the rows
+  int32_t row0_in;   // first row in the [n_rows, .] input/output of the call
+  int32_t rows;      // valid rows (<= BM)
+  int32_t row0_out;  // first row in the per-group saved activations (differs in shared mode)
+};
+
+// Device-built plan, laid out in the workspace.
+struct Plan {
+  RowTile* tiles;      // [max_tiles]
+  int32_t* n_tiles;    // [1]
+  int32_t* order;      // [n_groups] groups by descending row count (ties: ascending id)
+  int32_t* slot_of;    // [n_groups] compact slot of an active group, -1 otherwise
+  int32_t* counts;     // [n_groups]
+  int32_t* starts;     // [n_groups] first row of the group
+};
+
+inline size_t plan_bytes(int n_groups, int max_tiles) {
+  return align_up((size_t)max_tiles * sizeof(RowTile), 256) + 256 + 4 * align_up((size_t)n_groups * 4, 256);
+}
+
+inline Plan carve_plan(void* ws, int n_groups, int max_tiles) {
+  char* p = (char*)ws;
+  Plan pl;
+  pl.tiles = (RowTile*)p;
+  p += align_up((size_t)max_tiles * sizeof(RowTile), 256);
+  pl.n_tiles = (int32_t*)p;
+  p += 256;
+  size_t g = align_up((size_t)n_groups * 4, 256);
+  pl.order = (int32_t*)p;
+  p += g;
+  pl.slot_of = (int32_t*)p;
+  p += g;
+  pl.counts = (int32_t*)p;
+  p += g;
+  pl.starts = (int32_t*)p;
+  return pl;
+}
+
+// C[rows, N] (+ second C when dual) = sum over (pair, seg) of A_seg[rows, K] * B_seg[K, N]
+struct RowGemm {
+  const RowTile* tiles;     // NULL: direct tiling of n_rows rows, single group 0
+  const int32_t* n_tiles;
+  int32_t n_rows;
+  int32_t N, K;
+  int32_t n_pairs, n_segs;
+  const void* A[2];         // per pair; element (row, k) at A + seg*a_seg + row*lda + k
+  int64_t lda, a_seg;
+  int32_t a_rows_out;       // A rows are indexed by row0_out (saved activations) instead of row0_in
+  const void* B[2];         // per pair; + group*b_group + seg*b_seg
+  const void* Bdual;        // second B of a dual GEMM (pair 0 only)
+  int64_t ldb, b_group, b_seg;
+  // epilogue
+  void* out[3];
+  const void* in[2];
+  int64_t ldc;
+  int32_t c_rows_out;       // outputs indexed by row0_out
+};
+
+// per group: C[M, N] = A_g^T B_g over the rows of the group (K = rows of the group)
+struct WGemm {
+  const int32_t* order;     // NULL: identity
+  const int32_t* slot_of;   // NULL: slot = group
+  const int32_t* counts;    // NULL: every group has n_rows rows
+  const int32_t* starts;
+  int32_t n_rows;
+  int32_t M, N;
+  const void* A;            // element (row, m) at A + row*lda + m
+  int64_t lda;
+  int32_t a_per_group;      // shared mode: A rows of group g start at g*n_rows
+  const void* B[2];         // element (row, n) at B + row*ldb + n; B[1] for the dual GEMM
+  int64_t ldb;
+  int32_t b_per_group;
+  void* C[2];
+  int64_t c_slot;           // elements per slot
+};
+
+}  // namespace moe
