@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+One "step" is one forward+backward pass of the whole path (route, dispatch, routed and shared
+expert grouped GEMMs, combine; combine-bwd, dH/dX/dW grouped GEMMs with compacted dW, un-permute)
+over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config dsv3|qwen|phi|stress|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TF = 2500.0   # dense bf16 matrix peak, published
+FP32_VEC_PEAK_TF = 157.3
+
+GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx", "gemm_bwd_dwd", "gemm_bwd_dwgu")
+# kernel symbol behind each profiling label (as rocprofv3 --kernel-trace --stats names them)
+SYMBOL = {
+    "gemm_fwd_gate_up": "row_gemm_kernel<Core<NB=2,A_KC,B rows>, EPI_SWIGLU_FWD>",
+    "gemm_fwd_down": "row_gemm_kernel<Core<NB=1,A_KC,B rows>, EPI_STORE>",
+    "gemm_bwd_dh": "row_gemm_kernel<Core<NB=1,A_KC,B_KC>, EPI_SWIGLU_BWD>",
+    "gemm_bwd_dx": "row_gemm_kernel<Core<NB=1,A_KC,B_KC>, EPI_STORE>",
+    "gemm_bwd_dwd": "w_gemm_kernel<Core<NB=1>>",
+    "gemm_bwd_dwgu": "w_gemm_kernel<Core<NB=2>>",
+}
+
+
+def algorithmic_work(cfg: wl.MoEConfig):
+    """Per step: FLOPs of each GEMM label over real rows only, bytes of each streaming kernel."""
+    b = 4 if cfg.dtype == "f32" else 2
+    A, T, d, F, k = cfg.A, cfg.T, cfg.d, cfg.d_ff, cfg.k
+    routed = A * d * F
+    shared = cfg.n_shared * T * d * cfg.d_ff_shared
+    unit = routed + shared
+    flops = {"gemm_fwd_gate_up": 4.0 * unit, "gemm_fwd_down": 2.0 * unit, "gemm_bwd_dh": 2.0 * unit,
+             "gemm_bwd_dx": 4.0 * unit, "gemm_bwd_dwd": 2.0 * unit, "gemm_bwd_dwgu": 4.0 * unit}
+    has_sh = 1 if cfg.n_shared else 0
+    byts = {
+        "route_kernel": T * cfg.E * 4 + T * k * 8,
+        "dispatch_rows": (1 + k) * T * d * b + A * 4,
+        # two launches per step: Y (weights, + shared output) and dX (unit weights, + shared dX)
+        "combine_kernel": 2 * ((k + 1 + has_sh) * T * d * b + A * 4) + A * 4,
+        "combine_bwd_kernel": (1 + 2 * k) * T * d * b + A * 12,
+    }
+    return flops, byts
+
+
+class LazyExperts:
+    """Expert weights that stay on the GPU; the oracle receives one expert at a time as fp32 numpy."""
+
+    def __init__(self, w: torch.Tensor):
+        self.w = w
+
+    def __len__(self):
+        return self.w.shape[0]
+
+    def __getitem__(self, e):
+        return self.w[int(e)].float().cpu().numpy()
+
+
+def cpu_baseline(cfg, inp, weights, budget_tokens):
+    """Times the oracle, as it stands, on the first `budget_tokens` tokens of the same workload."""
+    from oracle import moe_oracle as orc
+
+    n = min(budget_tokens, cfg.T)
+    lg = inp["logits"][:n].numpy()
+    X = inp["X"][:n].float().numpy()
+    dY = inp["dY"][:n].float().numpy()
+    W = {k: LazyExperts(v) for k, v in weights.items()}
+    t0 = time.perf_counter()
+    orc.layer_fwd_bwd(lg, X, dY, W["Wg"], W["Wu"], W["Wd"], cfg.k, cfg.gate, cfg.renorm,
+                      W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
+    dt = time.perf_counter() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"first {n} of {cfg.T} tokens of the same workload, fwd+bwd, fp64 numpy oracle, {dt:.1f} s"}
+
+
+CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 96, "phi": 48, "dsv3": 8, "stress": 96}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="dsv3", choices=list(wl.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the one-GPU hot path; it has no multi-GPU mode (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    import paper_2502_02581_amd as moe
+
+    cfg = wl.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    inp = {"logits": wl.make_logits(cfg), "X": wl.make_tokens(cfg), "dY": wl.make_grad_out(cfg)}
+    weights = wl.make_weights(cfg, dev)
+    g = {k: v.to(dev) for k, v in inp.items()}
+    shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev)
+    sh = [weights.get("Wsg"), weights.get("Wsu"), weights.get("Wsd")]
+
+    def step():
+        hp.forward(g["logits"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
+        hp.backward(g["dY"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    moe.moe_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = moe.moe_profile_report()
+    moe.moe_profile_enable(False)
+
+    ms_per_step = dt / args.steps * 1e3
+    flops, byts = algorithmic_work(cfg)
+    kernels = {}
+    for label, (n, ms) in prof.items():
+        per_step_ms = ms / args.steps
+        ent = {"launches_per_step": n / args.steps, "ms_per_step": round(per_step_ms, 4)}
+        if label in flops and per_step_ms > 0:
+            ent["tflops"] = round(flops[label] / (per_step_ms * 1e-3) / 1e12, 2)
+            ent["frac_mfma_peak"] = round(ent["tflops"] / (MFMA_BF16_PEAK_TF if cfg.dtype == "bf16" else FP32_VEC_PEAK_TF), 4)
+        if label in byts and per_step_ms > 0:
+            ent["gbs"] = round(byts[label] / (per_step_ms * 1e-3) / 1e9, 1)
+            ent["frac_hbm_peak"] = round(ent["gbs"] / HBM_PEAK_GBS, 4)
+        kernels[label] = ent
+    gemm_ms = sum(kernels[l]["ms_per_step"] for l in GEMM_LABELS if l in kernels)
+    gemm_tflops = sum(flops.values()) / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    dom = max((l for l in GEMM_LABELS if l in kernels), key=lambda l: kernels[l]["ms_per_step"])
+    dom_n, dom_ms = prof[dom]
+    peak = MFMA_BF16_PEAK_TF if cfg.dtype == "bf16" else FP32_VEC_PEAK_TF
+    achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": dom, "symbol": SYMBOL[dom],
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
+                "flop_per_launch_avg": flops[dom] * args.steps / dom_n, "traffic": None}
+
+    counts = hp.b["counts"].cpu()
+    out = {
+        "metric": "moe_layer_fwd_bwd_tokens_per_s", "value": round(cfg.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} top-{cfg.k} {cfg.gate} d_ff={cfg.d_ff} "
+                               f"shared={cfg.n_shared}x{cfg.d_ff_shared} routing={cfg.routing}(s={cfg.zipf_s}) seed={cfg.seed}",
+                   "active_experts": int((counts > 0).sum()), "max_rows": int(counts.max()),
+                   "load_share_std": round(float((counts.double() / counts.sum()).std(unbiased=False)), 5)},
+        "grouped_gemm_tflops": round(gemm_tflops, 2), "grouped_gemm_frac_mfma_peak": round(gemm_tflops / peak, 4),
+        "total_tflops": round(cfg.flops()["total"] / (ms_per_step * 1e-3) / 1e12, 2),
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, weights, CPU_SAMPLE_TOKENS[cfg.name])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

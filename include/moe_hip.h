@@ -164,6 +164,18 @@ int moe_combine(const moe_shape_t* shape, const void* Yp, const int32_t* row_of,
 int moe_combine_bwd(const moe_shape_t* shape, const void* dY, const void* Yp, const int32_t* row_of,
                     const float* topk_w, void* dYp, float* dw, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the hot path; off by default).
+ * moe_profile_enable(1) clears earlier records and makes every later kernel launch of this
+ * library be bracketed by two HIP events on the launch's own stream; moe_profile_enable(0)
+ * stops recording.  moe_profile_report waits for the recorded events and writes one line per
+ * kernel label, "<label> <launches> <total milliseconds>\n", into the HOST buffer `buf`
+ * (truncated to buf_bytes, always NUL-terminated); it returns the size needed for the whole
+ * report.  Not thread-safe against concurrent launches.
+ */
+int moe_profile_enable(int on);
+size_t moe_profile_report(char* buf, size_t buf_bytes);
+
 #ifdef __cplusplus
 }
 #endif

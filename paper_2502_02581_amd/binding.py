@@ -16,7 +16,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
 EXPORTS = ["moe_abi_version", "moe_last_error", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
-           "moe_combine", "moe_combine_bwd"]
+           "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report"]
 
 
 class MoEError(RuntimeError):
@@ -84,6 +84,10 @@ def load_library():
     lib.moe_combine.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.moe_combine_bwd.restype = ctypes.c_int
     lib.moe_combine_bwd.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp]
+    lib.moe_profile_enable.restype = ctypes.c_int
+    lib.moe_profile_enable.argtypes = [ctypes.c_int]
+    lib.moe_profile_report.restype = sz
+    lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
     _lib = lib
     return lib
 
@@ -184,6 +188,22 @@ def moe_combine_bwd(shape: MoEShape, dY, Yp, row_of, topk_w, dYp, dw, stream=Non
                                         _ptr(row_of, torch.int32, "row_of"), _ptr(topk_w, torch.float32, "topk_w"),
                                         _ptr(dYp, dt, "dYp"), _ptr(dw, torch.float32, "dw"), _stream(stream))
     _check(rc, "moe_combine_bwd")
+
+
+def moe_profile_enable(on: bool):
+    load_library().moe_profile_enable(int(on))
+
+
+def moe_profile_report() -> Dict[str, tuple]:
+    """{kernel label: (launches, total milliseconds)} of the launches recorded since enable."""
+    lib = load_library()
+    buf = ctypes.create_string_buffer(1 << 16)
+    lib.moe_profile_report(buf, len(buf))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        label, n, ms = line.split()
+        out[label] = (int(n), float(ms))
+    return out
 
 
 class MoEHotPath:

@@ -83,6 +83,7 @@ extern "C" int moe_combine(const moe_shape_t* shape, const void* Yp, const int32
     return MOE_EINVAL;
   }
   hipStream_t st = (hipStream_t)stream;
+  ProfScope prof("combine_kernel", st);
   if (shape->dtype == MOE_F32)
     hipLaunchKernelGGL(combine_kernel<float>, dim3(shape->T), dim3(256), 0, st, (const float*)Yp, row_of, topk_w,
                        (const float*)Yadd, (float*)Y, shape->d, shape->k);
@@ -107,6 +108,7 @@ extern "C" int moe_combine_bwd(const moe_shape_t* shape, const void* dY, const v
     return MOE_EINVAL;
   }
   hipStream_t st = (hipStream_t)stream;
+  ProfScope prof("combine_bwd_kernel", st);
   if (shape->dtype == MOE_F32)
     hipLaunchKernelGGL(combine_bwd_kernel<float>, dim3(shape->T), dim3(256), 0, st, (const float*)dY,
                        (const float*)Yp, row_of, topk_w, (float*)dYp, dw, shape->d, shape->k);

@@ -2,6 +2,10 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <mutex>
+#include <string>
+#include <vector>
+
 #include "moe_common.h"
 
 namespace moe {
@@ -55,7 +59,87 @@ int launch_status(const char* who) {
   return MOE_OK;
 }
 
+// ---- profiling records -----------------------------------------------------------------------
+struct ProfRec {
+  const char* label;
+  hipEvent_t start, stop;
+};
+static std::mutex g_prof_mu;
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof;
+static std::vector<hipEvent_t> g_event_pool;
+
+bool profile_on() { return g_prof_on; }
+
+static hipEvent_t take_event() {
+  if (!g_event_pool.empty()) {
+    hipEvent_t e = g_event_pool.back();
+    g_event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+void profile_push(const char* label, hipStream_t st, bool begin) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (begin) {
+    ProfRec r = {label, take_event(), take_event()};
+    (void)hipEventRecord(r.start, st);
+    g_prof.push_back(r);
+  } else {
+    for (size_t i = g_prof.size(); i-- > 0;)
+      if (g_prof[i].label == label) {
+        (void)hipEventRecord(g_prof[i].stop, st);
+        break;
+      }
+  }
+}
+
 }  // namespace moe
+
+extern "C" int moe_profile_enable(int on) {
+  using namespace moe;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  for (auto& r : g_prof) {
+    g_event_pool.push_back(r.start);
+    g_event_pool.push_back(r.stop);
+  }
+  g_prof.clear();
+  g_prof_on = on != 0;
+  return MOE_OK;
+}
+
+extern "C" size_t moe_profile_report(char* buf, size_t buf_bytes) {
+  using namespace moe;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  struct Agg { std::string label; int n; double ms; };
+  std::vector<Agg> agg;
+  for (auto& r : g_prof) {
+    if (hipEventSynchronize(r.stop) != hipSuccess) continue;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) continue;
+    size_t i = 0;
+    for (; i < agg.size(); i++)
+      if (agg[i].label == r.label) break;
+    if (i == agg.size()) agg.push_back({r.label, 0, 0.0});
+    agg[i].n++;
+    agg[i].ms += ms;
+  }
+  std::string out;
+  char line[160];
+  for (auto& a : agg) {
+    snprintf(line, sizeof(line), "%s %d %.6f\n", a.label.c_str(), a.n, a.ms);
+    out += line;
+  }
+  if (buf && buf_bytes > 0) {
+    size_t n = out.size() < buf_bytes - 1 ? out.size() : buf_bytes - 1;
+    memcpy(buf, out.data(), n);
+    buf[n] = 0;
+  }
+  return out.size() + 1;
+}
 
 extern "C" int moe_abi_version(void) { return MOE_ABI_VERSION; }
 extern "C" const char* moe_last_error(void) { return moe::g_err; }

@@ -155,12 +155,20 @@ extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32
   const int n_chunks = (A + kChunk - 1) / kChunk;
   int32_t* hist = (int32_t*)ws;
   if (n_chunks > 0) {
+    ProfScope prof("dispatch_count", st);
     hipLaunchKernelGGL(dispatch_count, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist);
   }
-  hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(1024), 0, st, hist, n_chunks, shape->E, counts, offsets);
+  {
+    ProfScope prof("dispatch_scan", st);
+    hipLaunchKernelGGL(dispatch_scan, dim3(1), dim3(1024), 0, st, hist, n_chunks, shape->E, counts, offsets);
+  }
   if (n_chunks > 0) {
-    hipLaunchKernelGGL(dispatch_rank, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist, offsets,
-                       row_of, src_of);
+    {
+      ProfScope prof("dispatch_rank", st);
+      hipLaunchKernelGGL(dispatch_rank, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist, offsets,
+                         row_of, src_of);
+    }
+    ProfScope prof("dispatch_rows", st);
     const int vec_per_row = (int)((size_t)shape->d * elem_size(shape->dtype) / 16);
     hipLaunchKernelGGL(dispatch_rows, dim3(shape->T), dim3(256), 0, st, (const uint4*)X, row_of, shape->k,
                        vec_per_row, (uint4*)Xp);

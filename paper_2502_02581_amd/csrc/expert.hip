@@ -230,7 +230,7 @@ static int max_row_tiles(int n_groups, int n_rows, bool shared, int BM) {
 }
 
 template <class Core, int NB, int EPI, bool B_KC>
-static void launch_row(const RowGemm& p, int max_tiles, hipStream_t st) {
+static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipStream_t st) {
   const int ntn = ceil_div(p.N, Core::BN);
   const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, Core::BM);
   if (n_mt == 0 || ntn == 0) return;
@@ -240,11 +240,12 @@ static void launch_row(const RowGemm& p, int max_tiles, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
     attr_done = true;
   }
+  ProfScope prof(label, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)(n_mt * ntn)), dim3(256), Core::LDS_BYTES, st, p);
 }
 
 template <class Core, int NB>
-static void launch_w(const WGemm& p, int n_groups, hipStream_t st) {
+static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_t st) {
   const int tiles = ceil_div(p.M, Core::BM) * ceil_div(p.N, Core::BN);
   if (tiles == 0 || n_groups == 0) return;
   auto kern = w_gemm_kernel<Core, NB>;
@@ -253,6 +254,7 @@ static void launch_w(const WGemm& p, int n_groups, hipStream_t st) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
     attr_done = true;
   }
+  ProfScope prof(label, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups), dim3(256), Core::LDS_BYTES, st, p);
 }
 
@@ -270,8 +272,11 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   const bool shared = a.offsets == nullptr;
   const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
-                     (int32_t*)nullptr, (int32_t*)nullptr);
+  {
+    ProfScope prof("plan_kernel", st);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+                       (int32_t*)nullptr, (int32_t*)nullptr);
+  }
   // F4: dual GEMM with the SwiGLU epilogue
   RowGemm p = {};
   p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
@@ -279,7 +284,7 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   p.A[0] = a.Xin; p.lda = a.d; p.a_seg = 0; p.a_rows_out = 0;
   p.B[0] = a.Wg; p.Bdual = a.Wu; p.ldb = a.F; p.b_group = (int64_t)a.d * a.F; p.b_seg = 0;
   p.out[0] = a.G; p.out[1] = a.U; p.out[2] = a.H; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<typename C::template core<2, true, false>, 2, EPI_SWIGLU_FWD, false>(p, max_tiles, st);
+  launch_row<typename C::template core<2, true, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
   // F5: Yout = H Wd (shared mode: summed over groups through K segments)
   RowGemm q = {};
   q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 1;
@@ -292,7 +297,7 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   } else {
     q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.F * a.d;
   }
-  launch_row<typename C::template core<1, true, false>, 1, EPI_STORE, false>(q, max_tiles, st);
+  launch_row<typename C::template core<1, true, false>, 1, EPI_STORE, false>("gemm_fwd_down", q, max_tiles, st);
 }
 
 struct BwdArgs {
@@ -316,8 +321,11 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   const size_t act_rows = (size_t)(shared ? a.n_groups : 1) * a.n_rows;
   char* dG = (char*)a.ws + a.plan_sz;
   char* dU = dG + align_up(act_rows * a.F * es, 256);
-  hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
-                     a.active_ids, a.n_active);
+  {
+    ProfScope prof("plan_kernel", st);
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+                       a.active_ids, a.n_active);
+  }
   // B2a: dH = dYin Wd^T, epilogue turns it into dG, dU
   RowGemm p = {};
   p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
@@ -325,7 +333,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   p.A[0] = a.dYin; p.lda = a.d; p.a_rows_out = 0;
   p.B[0] = a.Wd; p.ldb = a.d; p.b_group = (int64_t)a.F * a.d;
   p.in[0] = a.G; p.in[1] = a.U; p.out[0] = dG; p.out[1] = dU; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<typename C::template core<1, true, true>, 1, EPI_SWIGLU_BWD, true>(p, max_tiles, st);
+  launch_row<typename C::template core<1, true, true>, 1, EPI_SWIGLU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
   // B2b: dXin = dG Wg^T + dU Wu^T
   RowGemm q = {};
   q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 2;
@@ -338,7 +346,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   } else {
     q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.d * a.F;
   }
-  launch_row<typename C::template core<1, true, true>, 1, EPI_STORE, true>(q, max_tiles, st);
+  launch_row<typename C::template core<1, true, true>, 1, EPI_STORE, true>("gemm_bwd_dx", q, max_tiles, st);
   // B3: weight gradients, compacted to active groups, largest group first
   WGemm w = {};
   w.order = pl.order; w.slot_of = pl.slot_of; w.counts = pl.counts; w.starts = pl.starts; w.n_rows = a.n_rows;
@@ -346,14 +354,14 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   w.A = a.H; w.lda = a.F; w.a_per_group = shared;
   w.B[0] = a.dYin; w.ldb = a.d; w.b_per_group = 0;
   w.C[0] = a.dWd; w.c_slot = (int64_t)a.F * a.d;
-  launch_w<typename C::template core<1, false, false>, 1>(w, a.n_groups, st);
+  launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
   WGemm v = {};
   v.order = pl.order; v.slot_of = pl.slot_of; v.counts = pl.counts; v.starts = pl.starts; v.n_rows = a.n_rows;
   v.M = a.d; v.N = a.F;
   v.A = a.Xin; v.lda = a.d; v.a_per_group = 0;
   v.B[0] = dG; v.B[1] = dU; v.ldb = a.F; v.b_per_group = shared;
   v.C[0] = a.dWg; v.C[1] = a.dWu; v.c_slot = (int64_t)a.d * a.F;
-  launch_w<typename C::template core<2, false, false>, 2>(v, a.n_groups, st);
+  launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
 }
 
 static size_t plan_size_for(const moe_shape_t* s, int n_groups, int n_rows, bool shared) {

@@ -17,6 +17,21 @@ int check_shape(const moe_shape_t* s, const char* who);
 bool aligned16(const void* p);
 int launch_status(const char* who);
 
+// ---- optional per-kernel timing (off by default): HIP events around every launch ------------
+bool profile_on();
+void profile_push(const char* label, hipStream_t st, bool begin);
+struct ProfScope {
+  const char* label;
+  hipStream_t st;
+  bool on;
+  ProfScope(const char* l, hipStream_t s) : label(l), st(s), on(profile_on()) {
+    if (on) profile_push(label, st, true);
+  }
+  ~ProfScope() {
+    if (on) profile_push(label, st, false);
+  }
+};
+
 inline size_t elem_size(int dtype) { return dtype == MOE_F32 ? 4 : 2; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

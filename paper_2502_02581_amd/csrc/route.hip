@@ -95,6 +95,7 @@ extern "C" int moe_route(const moe_shape_t* shape, const float* logits, int32_t*
   hipStream_t st = (hipStream_t)stream;
   dim3 grid((shape->T + 3) / 4), block(256);
   const int E = shape->E;
+  ProfScope prof("route_kernel", st);
 #define MOE_ROUTE(R)                                                                                  \
   hipLaunchKernelGGL(route_kernel<R>, grid, block, 0, st, logits, topk_idx, topk_w, shape->T, E, shape->k, \
                      shape->gate, shape->renorm)
