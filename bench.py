@@ -88,7 +88,7 @@ def cpu_baseline(cfg, inp, weights, budget_tokens):
             "sample": f"first {n} of {cfg.T} tokens of the same workload, fwd+bwd, fp64 numpy oracle, {dt:.1f} s"}
 
 
-CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 96, "phi": 48, "dsv3": 8, "stress": 96}
+CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 96, "phi": 48, "dsv3": 32, "stress": 96}
 
 
 def main():
