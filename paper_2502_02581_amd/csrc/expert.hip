@@ -111,7 +111,16 @@ template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float
 
 enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2 };
 
-__device__ __forceinline__ float sigmoidf_(float z) { return 1.f / (1.f + expf(-z)); }
+__device__ __forceinline__ uint32_t clip_u32(int64_t v) {
+  return v < 0 ? 0u : v > 0xffffffffll ? 0xffffffffu : (uint32_t)v;
+}
+
+// precise for the fp32 path; hardware exp and reciprocal where the result is rounded to bf16 anyway
+template <typename T> __device__ __forceinline__ float sigmoidf_(float z);
+template <> __device__ __forceinline__ float sigmoidf_<float>(float z) { return 1.f / (1.f + expf(-z)); }
+template <> __device__ __forceinline__ float sigmoidf_<bf16_t>(float z) {
+  return __builtin_amdgcn_rcpf(1.f + __expf(-z));
+}
 
 // --------------------------------------------------------------------- row-tiled GEMM kernel
 template <class Core, int NB, int EPI, bool B_KC>
@@ -137,7 +146,7 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
   const int a_row0 = p.a_rows_out ? t.row0_out : t.row0_in;
   const int nk = (p.K + BK - 1) / BK;
   const int per_pair = p.n_segs * nk;
-  auto src = [&](int it) {
+  auto src = [&](int it) __attribute__((always_inline)) {
     IterSrc<T, NB> s;
     const int pair = it / per_pair, rem = it % per_pair;
     const int seg = rem / nk, k0 = (rem % nk) * BK;
@@ -146,10 +155,16 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
     s.b[0] = (const T*)p.B[pair] + boff;
     if (NB == 2) s.b[NB - 1] = (const T*)p.Bdual + boff;
     s.k_left = p.K - k0;
+    const int64_t es = sizeof(T);
+    const int64_t ab = ((int64_t)(t.rows - 1) * p.lda + (p.K - k0)) * es;
+    const int64_t bb = B_KC ? ((int64_t)(n_valid - 1) * p.ldb + (p.K - k0)) * es
+                            : ((int64_t)(p.K - k0 - 1) * p.ldb + (p.N - n0)) * es;
+    s.a_bytes = clip_u32(ab);
+    s.b_bytes = clip_u32(bb);
     return s;
   };
   const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
-  auto epi = [&](int m, int n, const float (&v)[NB][4]) {
+  auto epi = [&](int m, int n, const float (&v)[NB][4]) __attribute__((always_inline)) {
     if (m >= t.rows || n >= n_valid) return;
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
     if (EPI == EPI_STORE) {
@@ -157,7 +172,7 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[4];
 #pragma unroll
-      for (int q = 0; q < 4; q++) h[q] = v[0][q] * sigmoidf_(v[0][q]) * v[NB - 1][q];
+      for (int q = 0; q < 4; q++) h[q] = v[0][q] * sigmoidf_<T>(v[0][q]) * v[NB - 1][q];
       store4<T>((T*)p.out[0] + off, v[0]);
       store4<T>((T*)p.out[1] + off, v[NB - 1]);
       store4<T>((T*)p.out[2] + off, h);
@@ -167,7 +182,7 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
       load4<T>((const T*)p.in[1] + off, u);
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        const float s = sigmoidf_(g[q]);
+        const float s = sigmoidf_<T>(g[q]);
         du[q] = v[0][q] * g[q] * s;
         dg[q] = v[0][q] * u[q] * s * (1.f + g[q] * (1.f - s));
       }
@@ -194,16 +209,19 @@ __global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
   const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
   const int a_row0 = start + (p.a_per_group ? g * p.n_rows : 0);
   const int b_row0 = start + (p.b_per_group ? g * p.n_rows : 0);
-  auto src = [&](int it) {
+  auto src = [&](int it) __attribute__((always_inline)) {
     IterSrc<T, NB> s;
     const int k0 = it * BK;
     s.a = (const T*)p.A + (int64_t)(a_row0 + k0) * p.lda + m0;
     s.b[0] = (const T*)p.B[0] + (int64_t)(b_row0 + k0) * p.ldb + n0;
     if (NB == 2) s.b[NB - 1] = (const T*)p.B[1] + (int64_t)(b_row0 + k0) * p.ldb + n0;
     s.k_left = K - k0;
+    const int64_t es = sizeof(T);
+    s.a_bytes = clip_u32(((int64_t)(K - k0 - 1) * p.lda + (p.M - m0)) * es);
+    s.b_bytes = clip_u32(((int64_t)(K - k0 - 1) * p.ldb + (p.N - n0)) * es);
     return s;
   };
-  auto epi = [&](int m, int n, const float (&v)[NB][4]) {
+  auto epi = [&](int m, int n, const float (&v)[NB][4]) __attribute__((always_inline)) {
     if (m >= m_valid || n >= n_valid) return;
     const int64_t off = (int64_t)slot * p.c_slot + (int64_t)(m0 + m) * p.N + n0 + n;
     store4<T>((T*)p.C[0] + off, v[0]);
@@ -213,15 +231,31 @@ __global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
 }
 
 // ------------------------------------------------------------------------------ host side
-template <int DT> struct Cores;
-template <> struct Cores<MOE_F32> {
+// Three families of tile cores: fp32 FMA (MOE_F32), the general bf16 MFMA core (any d, d_ff that are
+// multiples of 8) and the bf16 core with LDS DMA loads (d and d_ff multiples of 64).
+enum { PATH_F32 = 0, PATH_BF16 = 1, PATH_BF16_DMA = 2 };
+template <int PATH> struct Cores;
+template <> struct Cores<PATH_F32> {
   static constexpr int BM = 64, BN = 64;
   template <int NB, bool A_KC, bool B_KC> using core = F32Core<NB, A_KC, B_KC>;
 };
-template <> struct Cores<MOE_BF16> {
+template <> struct Cores<PATH_BF16> {
   static constexpr int BM = 128, BN = 128;
-  template <int NB, bool A_KC, bool B_KC> using core = MfmaCore<128, 128, NB, A_KC, B_KC>;
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaCore<128, 128, NB, A_KC, B_KC, 2, 2>;
 };
+template <> struct Cores<PATH_BF16_DMA> {
+  static constexpr int BM = 256, BN = 256;
+  // one block computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each of the two products)
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 2>;
+};
+
+static int pick_path(const moe_shape_t* s) {
+  if (s->dtype == MOE_F32) return PATH_F32;
+  return (s->d % 64 == 0 && s->d_ff % 64 == 0) ? PATH_BF16_DMA : PATH_BF16;
+}
+static int path_bm(int path) {
+  return path == PATH_F32 ? Cores<PATH_F32>::BM : path == PATH_BF16 ? Cores<PATH_BF16>::BM : Cores<PATH_BF16_DMA>::BM;
+}
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -266,9 +300,9 @@ struct FwdArgs {
   void* ws;
 };
 
-template <int DT>
+template <int PATH>
 static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
-  typedef Cores<DT> C;
+  typedef Cores<PATH> C;
   const bool shared = a.offsets == nullptr;
   const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
@@ -311,11 +345,11 @@ struct BwdArgs {
   size_t plan_sz;
 };
 
-template <int DT>
+template <int PATH>
 static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
-  typedef Cores<DT> C;
+  typedef Cores<PATH> C;
   const bool shared = a.offsets == nullptr;
-  const size_t es = elem_size(DT);
+  const size_t es = PATH == PATH_F32 ? 4 : 2;
   const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
   const size_t act_rows = (size_t)(shared ? a.n_groups : 1) * a.n_rows;
@@ -365,8 +399,8 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
 }
 
 static size_t plan_size_for(const moe_shape_t* s, int n_groups, int n_rows, bool shared) {
-  const int BM = s->dtype == MOE_F32 ? Cores<MOE_F32>::BM : Cores<MOE_BF16>::BM;
-  return align_up(plan_bytes(n_groups, max_row_tiles(n_groups, n_rows, shared, BM) + 1), 256);
+  // sized for the smallest row tile of any path, so the query does not depend on the path taken
+  return align_up(plan_bytes(n_groups, max_row_tiles(n_groups, n_rows, shared, 64) + 1), 256);
 }
 
 static int check_expert_args(const moe_shape_t* s, int n_groups, int n_rows, const char* who) {
@@ -421,8 +455,11 @@ extern "C" int moe_expert_fwd(const moe_shape_t* shape, int32_t n_groups, const 
   }
   if (n_rows == 0) return MOE_OK;
   FwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xin, Wg, Wu, Wd, G, U, H, Yout, ws};
-  if (shape->dtype == MOE_F32) expert_fwd_impl<MOE_F32>(a, (hipStream_t)stream);
-  else expert_fwd_impl<MOE_BF16>(a, (hipStream_t)stream);
+  switch (pick_path(shape)) {
+    case PATH_F32: expert_fwd_impl<PATH_F32>(a, (hipStream_t)stream); break;
+    case PATH_BF16: expert_fwd_impl<PATH_BF16>(a, (hipStream_t)stream); break;
+    default: expert_fwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
+  }
   return launch_status("moe_expert_fwd");
 }
 
@@ -452,7 +489,10 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
   }
   BwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xin, Wg, Wu, Wd, G, U, H, dYin, dXin,
                active_ids, n_active, dWg_c, dWu_c, dWd_c, ws, plan_size_for(shape, n_groups, n_rows, offsets == nullptr)};
-  if (shape->dtype == MOE_F32) expert_bwd_impl<MOE_F32>(a, (hipStream_t)stream);
-  else expert_bwd_impl<MOE_BF16>(a, (hipStream_t)stream);
+  switch (pick_path(shape)) {
+    case PATH_F32: expert_bwd_impl<PATH_F32>(a, (hipStream_t)stream); break;
+    case PATH_BF16: expert_bwd_impl<PATH_BF16>(a, (hipStream_t)stream); break;
+    default: expert_bwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
+  }
   return launch_status("moe_expert_bwd");
 }

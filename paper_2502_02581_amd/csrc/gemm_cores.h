@@ -18,6 +18,9 @@ struct IterSrc {
   const T* a;        // A tile origin for this iteration (k offset included)
   const T* b[NB];    // B tile origin(s)
   int k_left;        // valid K elements from this origin on
+  // bytes from the origin to the end of the valid data of this tile (used by the cores that load
+  // through bounds-checked buffer descriptors: anything at or beyond reads as zero)
+  uint32_t a_bytes, b_bytes;
 };
 
 // ------------------------------------------------------------------------------ fp32 core
@@ -103,21 +106,22 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 //    (row/2)%8 so that the 16 rows one ds_read_b128 phase touches fall into distinct banks.
 //  row-contiguous operand ([K][rows] in memory): [64][rows + 32]; the 64-byte pad moves the four
 //    k rows of a transposing read (ds_read_b64_tr_b16) to four different bank quarters.
-template <int BM_, int BN_, int NB, bool A_KC, bool B_KC>
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2>
 struct MfmaCore {
   typedef bf16_t T;
   static constexpr int BM = BM_, BN = BN_, BK = 64, NT = 256;
-  static constexpr int WM = 2, WN = 2;
+  static constexpr int WM = WM_, WN = WN_;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static constexpr int PAD = 32;
-  static constexpr int A_LD = A_KC ? BK : BM + PAD;
-  static constexpr int B_LD = B_KC ? BK : BN + PAD;
-  static constexpr int A_ELEMS = A_KC ? BM * BK : BK * A_LD;
-  static constexpr int B_ELEMS = B_KC ? BN * BK : BK * B_LD;
-  static constexpr int LDS_BYTES = (A_ELEMS + NB * B_ELEMS) * 2;
-  static constexpr int A_VEC = BM * BK / 8 / NT;
-  static constexpr int B_VEC = BN * BK / 8 / NT;
-  static_assert(BM % 64 == 0 && BN % 64 == 0, "tile must be a multiple of 64");
+  static constexpr int A_ELEMS = A_KC ? BM * BK : BK * (BM + PAD);
+  static constexpr int B_ELEMS = B_KC ? BN * BK : BK * (BN + PAD);
+  static constexpr int STAGE_ELEMS = A_ELEMS + NB * B_ELEMS;
+  static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;  // two stages
+  static constexpr int A_VEC = (BM * BK / 8 + NT - 1) / NT;
+  static constexpr int B_VEC = (BN * BK / 8 + NT - 1) / NT;
+  static_assert(WM * WN == 4, "four wavefronts per block");
+  static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
   // ---- global -> registers (16 bytes per access), zero outside the valid extents
   template <int ROWS, int NVEC, bool KC>
@@ -129,7 +133,7 @@ struct MfmaCore {
       int row, kk;
       if (KC) { row = v / (BK / 8); kk = (v % (BK / 8)) * 8; }
       else { kk = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
-      const bool ok = row < rows_valid && kk < k_left;
+      const bool ok = row < rows_valid && kk < k_left && (ROWS * BK / 8 % NT == 0 || v < ROWS * BK / 8);
       const bf16_t* p = KC ? base + (int64_t)row * ld + kk : base + (int64_t)kk * ld + row;
       r[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
     }
@@ -140,6 +144,7 @@ struct MfmaCore {
 #pragma unroll
     for (int i = 0; i < NVEC; i++) {
       const int v = threadIdx.x + i * NT;
+      if (ROWS * BK / 8 % NT != 0 && v >= ROWS * BK / 8) continue;
       int off;
       if (KC) {
         const int row = v / (BK / 8), c = v % (BK / 8);
@@ -161,8 +166,8 @@ struct MfmaCore {
       const uint4 v = *reinterpret_cast<const uint4*>(lds + row * BK + ((c ^ ((row >> 1) & 7)) << 3));
       return __builtin_bit_cast(bf16x8_t, v);
     } else {
-      // transposing read: within 16 lanes, lane s reads 4 consecutive rows-elements at
-      // k = kb + s/4, column 4*(s%4); it receives k = kb..kb+3 of column s.
+      // transposing read: within 16 lanes, lane s points at 4 consecutive columns of row
+      // k = kb + s/4, starting at column 4*(s%4); it receives k = kb..kb+3 of column s.
       const int s = lane & 15;
       const int kb = ks * 16 + 8 * (lane >> 5);
       const int col = row0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
@@ -176,11 +181,33 @@ struct MfmaCore {
     }
   }
 
+  struct Frags {
+    bf16x8_t a[TM], b[NB][TN];
+  };
+  __device__ static __forceinline__ void load_frags(const bf16_t* As, const bf16_t* Bs, int wm0, int wn0, int ks,
+                                                    Frags& f) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) f.a[i] = frag<BM, A_KC>(As, wm0 + i * 32, ks);
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) f.b[nb][j] = frag<BN, B_KC>(Bs + nb * B_ELEMS, wn0 + j * 32, ks);
+  }
+  __device__ static __forceinline__ void mma(f32x16_t (&acc)[NB][TM][TN], const Frags& f) {
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          // operands exchanged: result register r of lane l is C[m = l%32][n = 8*(r/4) + 4*(l/32) + r%4]
+          acc[nb][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb][j], f.a[i], acc[nb][i][j], 0, 0, 0);
+  }
+
   template <class SrcFn, class Epi>
   __device__ static void run(char* smem, int n_iters, SrcFn src, int64_t lda, int64_t ldb, int m_valid,
                              int n_valid, Epi epi) {
-    bf16_t* As = (bf16_t*)smem;
-    bf16_t* Bs = As + A_ELEMS;
+    bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
 
@@ -195,42 +222,46 @@ struct MfmaCore {
           for (int r = 0; r < 16; r++) acc[nb][i][j][r] = 0.f;
 
     uint4 ra[A_VEC], rb[NB][B_VEC];
-    if (n_iters > 0) {
-      IterSrc<bf16_t, NB> s = src(0);
+    auto fetch = [&](int it) {
+      IterSrc<bf16_t, NB> s = src(it);
       gload<BM, A_VEC, A_KC>(s.a, lda, m_valid, s.k_left, ra);
 #pragma unroll
       for (int nb = 0; nb < NB; nb++) gload<BN, B_VEC, B_KC>(s.b[nb], ldb, n_valid, s.k_left, rb[nb]);
-    }
-    for (int it = 0; it < n_iters; it++) {
+    };
+    auto stash = [&](int stage) {
+      bf16_t* As = lds + stage * STAGE_ELEMS;
       sstore<BM, A_VEC, A_KC>(As, ra);
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) sstore<BN, B_VEC, B_KC>(Bs + nb * B_ELEMS, rb[nb]);
+      for (int nb = 0; nb < NB; nb++) sstore<BN, B_VEC, B_KC>(As + A_ELEMS + nb * B_ELEMS, rb[nb]);
+    };
+
+    if (n_iters > 0) {
+      fetch(0);
+      stash(0);
+      if (n_iters > 1) fetch(1);
       __syncthreads();
-      if (it + 1 < n_iters) {  // next tile travels while this one is multiplied
-        IterSrc<bf16_t, NB> s = src(it + 1);
-        gload<BM, A_VEC, A_KC>(s.a, lda, m_valid, s.k_left, ra);
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++) gload<BN, B_VEC, B_KC>(s.b[nb], ldb, n_valid, s.k_left, rb[nb]);
-      }
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ks++) {
-        bf16x8_t af[TM], bfr[NB][TN];
-#pragma unroll
-        for (int i = 0; i < TM; i++) af[i] = frag<BM, A_KC>(As, wm0 + i * 32, ks);
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-          for (int j = 0; j < TN; j++) bfr[nb][j] = frag<BN, B_KC>(Bs + nb * B_ELEMS, wn0 + j * 32, ks);
-#pragma unroll
-        for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-          for (int i = 0; i < TM; i++)
-#pragma unroll
-            for (int j = 0; j < TN; j++)
-              // operands exchanged: the result register r of lane l is C[m = l%32][n = 8*(r/4) + 4*(l/32) + r%4]
-              acc[nb][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[nb][j], af[i], acc[nb][i][j], 0, 0, 0);
-      }
+    }
+    Frags f0, f1;
+    if (n_iters > 0) load_frags(lds, lds + A_ELEMS, wm0, wn0, 0, f0);
+    for (int it = 0; it < n_iters; it++) {
+      const bf16_t* As = lds + (it & 1) * STAGE_ELEMS;
+      const bf16_t* Bs = As + A_ELEMS;
+      load_frags(As, Bs, wm0, wn0, 1, f1);
+      mma(acc, f0);
+      // the tile of iteration it+1 (in registers since the previous iteration) goes to the other
+      // stage; the tile of iteration it+2 starts its trip from HBM/L2
+      if (it + 1 < n_iters) stash((it + 1) & 1);
+      if (it + 2 < n_iters) fetch(it + 2);
+      load_frags(As, Bs, wm0, wn0, 2, f0);
+      mma(acc, f1);
+      load_frags(As, Bs, wm0, wn0, 3, f1);
+      mma(acc, f0);
+      mma(acc, f1);
       __syncthreads();
+      if (it + 1 < n_iters) {
+        const bf16_t* An = lds + ((it + 1) & 1) * STAGE_ELEMS;
+        load_frags(An, An + A_ELEMS, wm0, wn0, 0, f0);
+      }
     }
 #pragma unroll
     for (int i = 0; i < TM; i++)
@@ -243,6 +274,246 @@ struct MfmaCore {
           for (int nb = 0; nb < NB; nb++)
 #pragma unroll
             for (int q = 0; q < 4; q++) vals[nb][q] = acc[nb][i][j][4 * g + q];
+          epi(wm0 + i * 32 + (lane & 31), wn0 + j * 32 + 8 * g + 4 * (lane >> 5), vals);
+        }
+  }
+};
+
+// ------------------------------------------------------------------ bf16 MFMA core, LDS DMA loads
+// Same math as MfmaCore, but tiles travel HBM/L2 -> LDS directly (buffer_load_dwordx4 ... lds),
+// so no registers stage them.  Lane l of a wave-wide load lands at lds_base + 16*l, which fixes
+// each tile to whole 1 KB pieces per instruction; the swizzles are applied on the global side
+// (which 16-byte piece a lane fetches).  Out-of-range pieces read as zero through the buffer
+// descriptor's num_records, which provides the zero fill of ragged row and K tails.
+// Requires K-contiguous operands to have K % 64 == 0 (a K tail inside a row cannot be masked).
+//
+// LDS layouts (bf16 elements), BK = 64, no padding:
+//  K-contiguous operand [rows][64]: 16-byte piece c of a row sits at position c ^ ((row/2)%8).
+//  row-contiguous operand [64 k][ROWS]: piece c (8 columns) of k-row k sits at position
+//    c ^ (4*(k%4)), which spreads the four k rows of a transposing read over all banks.
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2>
+struct MfmaDmaCore {
+  typedef bf16_t T;
+  static constexpr int BM = BM_, BN = BN_, BK = 64, NT = 256;
+  static constexpr int WM = WM_, WN = WN_;
+  static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
+  static constexpr int STAGE_ELEMS = A_ELEMS + NB * B_ELEMS;
+  static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
+  static constexpr int A_NI = BM / 32, B_NI = BN / 32;  // wave-wide loads per wave and tile
+  static_assert(WM * WN == 4, "four wavefronts per block");
+  static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
+  static_assert(BM % 128 == 0 && BN % 128 == 0, "swizzle of row-contiguous tiles needs >= 16 pieces per k row");
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
+  typedef __attribute__((address_space(3))) void* lds_vptr;
+
+  // Byte offset (from the tile origin in memory) of the piece that lane `lane` of wave `wave`
+  // fetches with its FIRST load.  The j-th load of the same lane is j * load_stride() rows further
+  // on (the swizzle terms do not depend on j), so one offset register per operand is enough; the
+  // j-dependent part moves into the descriptor base, which keeps it inside the bounds check.
+  template <int ROWS, bool KC>
+  __device__ static __forceinline__ uint32_t piece_offset(int wave, int lane, uint32_t ld) {
+    const int q = wave * 64 + lane;  // linear 16-byte piece of the LDS tile
+    if (KC) {
+      const int row = q >> 3, pos = q & 7;
+      const int c = pos ^ ((row >> 1) & 7);
+      return (uint32_t)row * ld * 2u + (uint32_t)c * 16u;
+    } else {
+      constexpr int PR = ROWS / 8;
+      const int k = q / PR, pos = q % PR;
+      const int c = pos ^ (4 * (k & 3));
+      return (uint32_t)k * ld * 2u + (uint32_t)c * 16u;
+    }
+  }
+  // rows of the memory operand (K-contiguous: tile rows; row-contiguous: k rows) between two
+  // consecutive loads of a wave: four waves x 1 KB = 4 KB of LDS tile per round
+  template <int ROWS, bool KC>
+  __device__ static constexpr int load_stride() { return KC ? 32 : 2048 / ROWS; }
+
+  // NI wave-wide 16-byte-per-lane loads straight into LDS.  Written as inline assembly so that the
+  // compiler does not serialise them against the LDS reads of the other stage (it would wait for
+  // vmcnt(0) before every ds_read that may alias); run() waits for them itself before its barrier.
+  typedef __attribute__((ext_vector_type(4))) int rsrc_t;
+  template <int NI, int ROWS, bool KC>
+  __device__ static __forceinline__ void issue(const bf16_t* base, uint32_t bytes, uint32_t lds_tile_addr, int wave,
+                                               uint32_t voff, uint32_t ld) {
+    const uint32_t step = (uint32_t)load_stride<ROWS, KC>() * ld * 2u;  // bytes between two loads
+    uint64_t p = (uint64_t)base;
+#pragma unroll
+    for (int j = 0; j < NI; j++) {
+      // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, 32-bit data format
+      rsrc_t rsrc;
+      rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+      rsrc[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
+      rsrc[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+      rsrc[3] = 0x00020000;
+      const uint32_t dst = lds_tile_addr + (uint32_t)(j * 4 + wave) * 1024u;
+      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :
+                   : "s"(dst), "v"(voff), "s"(rsrc)
+                   : "memory");
+      p += step;
+      bytes = bytes > step ? bytes - step : 0u;
+    }
+  }
+
+  // ---- LDS -> MFMA fragment: lane l holds k = 16*ks + 8*(l/32) + 0..7 of row (row0 + l%32).
+  // All lane-dependent address arithmetic is done once (lane_offsets); inside the K loop a
+  // fragment address is a per-lane base plus a compile-time constant, which the LDS instructions
+  // carry in their offset field.
+  //   K-contiguous tile:   off[ks] for the wave's first 32 rows; 32 more rows = +32*64 elements
+  //                        (the swizzle (row/2)%8 repeats every 16 rows)
+  //   row-contiguous tile: off[t] for the t-th group of 32 columns at k-step 0;
+  //                        k-step ks = +16*ks*ROWS elements, second half of the 8 k = +4*ROWS
+  template <int ROWS, bool KC, int NTILE>
+  __device__ static __forceinline__ void lane_offsets(int w0, int lane, int (&off)[4]) {
+    if (KC) {
+      const int row = w0 + (lane & 31);
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) off[ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 1) & 7)) << 3);
+    } else {
+      // transposing read: within 16 lanes, lane s points at 4 consecutive columns of k-row
+      // kb + s/4, starting at column 4*(s%4); it receives k = kb..kb+3 of column s.
+      const int s = lane & 15;
+      const int k = 8 * (lane >> 5) + (s >> 2);
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        const int col = w0 + t * 32 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+        off[t] = k * ROWS + (((col >> 3) ^ (4 * (k & 3))) << 3) + (col & 7);
+      }
+    }
+  }
+  template <int ROWS, bool KC>
+  __device__ static __forceinline__ bf16x8_t frag(const bf16_t* tile, const int (&off)[4], int t, int ks) {
+    if (KC) {
+      const uint4 v = *reinterpret_cast<const uint4*>(tile + off[ks] + t * 32 * BK);
+      return __builtin_bit_cast(bf16x8_t, v);
+    } else {
+      typedef __attribute__((address_space(3))) short4_t* lds_ptr;
+      const bf16_t* p0 = tile + off[t] + ks * 16 * ROWS;
+      short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0));
+      short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p0 + 4 * ROWS));
+      short8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8_t, both);
+    }
+  }
+
+  struct Frags {
+    bf16x8_t a[TM], b[NB][TN];
+  };
+  __device__ static __forceinline__ void load_frags(const bf16_t* As, const int (&ao)[4], const int (&bo)[4], int ks,
+                                                    Frags& f) {
+    const bf16_t* Bs = As + A_ELEMS;
+#pragma unroll
+    for (int i = 0; i < TM; i++) f.a[i] = frag<BM, A_KC>(As, ao, i, ks);
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int j = 0; j < TN; j++) f.b[nb][j] = frag<BN, B_KC>(Bs + nb * B_ELEMS, bo, j, ks);
+  }
+  __device__ static __forceinline__ void mma(f32x16_t (&acc)[NB][TM][TN], const Frags& f) {
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[nb][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb][j], f.a[i], acc[nb][i][j], 0, 0, 0);
+  }
+
+  template <class SrcFn, class Epi>
+  __device__ static __forceinline__ void run(char* smem, int n_iters, SrcFn src, int64_t lda, int64_t ldb,
+                                             int m_valid, int n_valid, Epi epi) {
+    bf16_t* lds = (bf16_t*)smem;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
+
+    f32x16_t acc[NB][TM][TN];
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) acc[nb][i][j][r] = 0.f;
+
+    const uint32_t voa = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda);
+    const uint32_t vob = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb);
+
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+    auto fetch = [&](int it) __attribute__((always_inline)) {
+      IterSrc<bf16_t, NB> s = src(it);
+      const uint32_t As = lds_addr + (uint32_t)((it & 1) * STAGE_ELEMS * 2);
+      issue<A_NI, BM, A_KC>(s.a, s.a_bytes, As, wave, voa, (uint32_t)lda);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++)
+        issue<B_NI, BN, B_KC>(s.b[nb], s.b_bytes, As + (A_ELEMS + nb * B_ELEMS) * 2, wave, vob, (uint32_t)ldb);
+    };
+
+    if (n_iters > 0) fetch(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    static_assert(TM <= 4 && TN <= 4, "lane_offsets holds four tiles per operand");
+    int ao[4], bo[4];
+    lane_offsets<BM, A_KC, TM>(wm0, lane, ao);
+    lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
+    // One wave per SIMD issues in order, so the overlap of LDS reads with MFMAs has to be in the
+    // instruction stream itself: while the MFMAs of k-step ks run, the fragments of ks+1 are read,
+    // one LDS read after each MFMA.
+    constexpr int kReads = (A_KC ? TM : 2 * TM) + NB * (B_KC ? TN : 2 * TN);
+    constexpr int kMfma = NB * TM * TN;
+    auto interleave = [&]() __attribute__((always_inline)) {
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+      for (int r = 0; r < (kReads < kMfma ? kReads : kMfma); r++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+      }
+      if (kMfma > kReads) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
+      if (kReads > kMfma) __builtin_amdgcn_sched_group_barrier(0x100, kReads - kMfma, 0);
+#endif
+    };
+    for (int it = 0; it < n_iters; it++) {
+      const bf16_t* As = lds + (it & 1) * STAGE_ELEMS;
+      Frags f0, f1;
+      load_frags(As, ao, bo, 0, f0);
+      // issued behind the first LDS reads so that their latency is covered; the tile lands in the
+      // other stage while this one is multiplied
+      if (it + 1 < n_iters) fetch(it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      load_frags(As, ao, bo, 1, f1);
+      mma(acc, f0);
+      interleave();
+      load_frags(As, ao, bo, 2, f0);
+      mma(acc, f1);
+      interleave();
+      load_frags(As, ao, bo, 3, f1);
+      mma(acc, f0);
+      interleave();
+      mma(acc, f1);
+      __builtin_amdgcn_sched_barrier(0);
+      // the next tile must have landed, and every wave must be done reading this one
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+    }
+    // The accumulators live in AGPRs.  Each value is copied out right where it is needed (the
+    // volatile asm pins the order); left to itself the compiler copies all 256 at the loop exit,
+    // needs every arch VGPR for that and spills the loop's address registers.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");  // MFMA results must have retired
+#pragma unroll
+    for (int i = 0; i < TM; i++)
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+          float vals[NB][4];
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+            for (int q = 0; q < 4; q++)
+              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(vals[nb][q]) : "a"(acc[nb][i][j][4 * g + q]));
           epi(wm0 + i * 32 + (lane & 31), wn0 + j * 32 + 8 * g + 4 * (lane >> 5), vals);
         }
   }
