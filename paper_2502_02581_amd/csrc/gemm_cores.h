@@ -298,8 +298,12 @@ struct MfmaDmaCore {
   static constexpr int WM = WM_, WN = WN_;
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
-  static constexpr int STAGE_ELEMS = A_ELEMS + NB * B_ELEMS;
-  static constexpr int LDS_BYTES = 2 * STAGE_ELEMS * 2;
+  // LDS: a ring of three A tiles and a ring of two B tile sets.  The A tile of iteration t+2 is
+  // requested while the B tiles of t+1 are still landing, so the memory pipeline never runs dry
+  // at the per-iteration barrier.
+  static constexpr int A_SLOTS = 3, B_SLOTS = 2;
+  static constexpr int B_SET_ELEMS = NB * B_ELEMS;
+  static constexpr int LDS_BYTES = (A_SLOTS * A_ELEMS + B_SLOTS * B_SET_ELEMS) * 2;
   static constexpr int A_NI = BM / 32, B_NI = BN / 32;  // wave-wide loads per wave and tile
   static_assert(WM * WN == 4, "four wavefronts per block");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
@@ -330,31 +334,27 @@ struct MfmaDmaCore {
   template <int ROWS, bool KC>
   __device__ static constexpr int load_stride() { return KC ? 32 : 2048 / ROWS; }
 
-  // NI wave-wide 16-byte-per-lane loads straight into LDS.  Written as inline assembly so that the
-  // compiler does not serialise them against the LDS reads of the other stage (it would wait for
-  // vmcnt(0) before every ds_read that may alias); run() waits for them itself before its barrier.
+  // One wave-wide 16-byte-per-lane load straight into LDS: the n-th 1 KB piece of this wave's share
+  // of a tile.  Written as inline assembly so that the compiler does not serialise it against the
+  // LDS reads of the other stage (it would wait for vmcnt(0) before every ds_read that may alias);
+  // run() waits for the loads itself before its barrier.
   typedef __attribute__((ext_vector_type(4))) int rsrc_t;
-  template <int NI, int ROWS, bool KC>
-  __device__ static __forceinline__ void issue(const bf16_t* base, uint32_t bytes, uint32_t lds_tile_addr, int wave,
-                                               uint32_t voff, uint32_t ld) {
-    const uint32_t step = (uint32_t)load_stride<ROWS, KC>() * ld * 2u;  // bytes between two loads
-    uint64_t p = (uint64_t)base;
-#pragma unroll
-    for (int j = 0; j < NI; j++) {
-      // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, 32-bit data format
-      rsrc_t rsrc;
-      rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
-      rsrc[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
-      rsrc[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-      rsrc[3] = 0x00020000;
-      const uint32_t dst = lds_tile_addr + (uint32_t)(j * 4 + wave) * 1024u;
-      asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :
-                   : "s"(dst), "v"(voff), "s"(rsrc)
-                   : "memory");
-      p += step;
-      bytes = bytes > step ? bytes - step : 0u;
-    }
+  template <int ROWS, bool KC>
+  __device__ static __forceinline__ void issue_one(const bf16_t* base, uint32_t bytes, uint32_t lds_tile_addr, int wave,
+                                                   uint32_t voff, uint32_t ld, int j) {
+    const uint32_t skip = (uint32_t)(j * load_stride<ROWS, KC>()) * ld * 2u;  // bytes before the j-th load
+    const uint64_t p = (uint64_t)base + skip;
+    // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, 32-bit data format
+    rsrc_t rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
+    rsrc[2] = __builtin_amdgcn_readfirstlane((int)(bytes > skip ? bytes - skip : 0u));
+    rsrc[3] = 0x00020000;
+    const uint32_t dst = lds_tile_addr + (uint32_t)(j * 4 + wave) * 1024u;
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(dst), "v"(voff), "s"(rsrc)
+                 : "memory");
   }
 
   // ---- LDS -> MFMA fragment: lane l holds k = 16*ks + 8*(l/32) + 0..7 of row (row0 + l%32).
@@ -401,24 +401,28 @@ struct MfmaDmaCore {
   struct Frags {
     bf16x8_t a[TM], b[NB][TN];
   };
-  __device__ static __forceinline__ void load_frags(const bf16_t* As, const int (&ao)[4], const int (&bo)[4], int ks,
-                                                    Frags& f) {
-    const bf16_t* Bs = As + A_ELEMS;
-#pragma unroll
-    for (int i = 0; i < TM; i++) f.a[i] = frag<BM, A_KC>(As, ao, i, ks);
-#pragma unroll
-    for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-      for (int j = 0; j < TN; j++) f.b[nb][j] = frag<BN, B_KC>(Bs + nb * B_ELEMS, bo, j, ks);
+  // the r-th fragment load of a k-step: first the TM fragments of A, then the NB*TN of B
+  static constexpr int kFragLoads = TM + NB * TN;
+  __device__ static __forceinline__ void load_frag_n(const bf16_t* As, const bf16_t* Bs, const int (&ao)[4],
+                                                     const int (&bo)[4], int ks, int r, Frags& f) {
+    if (r < TM) {
+      f.a[r] = frag<BM, A_KC>(As, ao, r, ks);
+    } else {
+      const int nb = (r - TM) / TN, j = (r - TM) % TN;
+      f.b[nb][j] = frag<BN, B_KC>(Bs + nb * B_ELEMS, bo, j, ks);
+    }
   }
-  __device__ static __forceinline__ void mma(f32x16_t (&acc)[NB][TM][TN], const Frags& f) {
-#pragma unroll
-    for (int nb = 0; nb < NB; nb++)
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[nb][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb][j], f.a[i], acc[nb][i][j], 0, 0, 0);
+  // MFMA number m of a k-step.  Inline assembly with a memory clobber: the instruction stream of
+  // the K loop is then exactly the order written in run() (LDS reads, tile loads and MFMAs
+  // interleaved by hand), the compiler only allocates registers and inserts the waits.
+  // Operands exchanged: result register r of lane l is C[m = l%32][n = 8*(r/4) + 4*(l/32) + r%4].
+  static constexpr int kMfma = NB * TM * TN;
+  __device__ static __forceinline__ void mfma_n(f32x16_t (&acc)[NB][TM][TN], const Frags& f, int m) {
+    const int nb = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+                 : "+a"(acc[nb][i][j])
+                 : "v"(f.b[nb][j]), "v"(f.a[i])
+                 : "memory");
   }
 
   template <class SrcFn, class Epi>
@@ -441,63 +445,99 @@ struct MfmaDmaCore {
 
     const uint32_t voa = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda);
     const uint32_t vob = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb);
-
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    auto fetch = [&](int it) __attribute__((always_inline)) {
-      IterSrc<bf16_t, NB> s = src(it);
-      const uint32_t As = lds_addr + (uint32_t)((it & 1) * STAGE_ELEMS * 2);
-      issue<A_NI, BM, A_KC>(s.a, s.a_bytes, As, wave, voa, (uint32_t)lda);
-#pragma unroll
-      for (int nb = 0; nb < NB; nb++)
-        issue<B_NI, BN, B_KC>(s.b[nb], s.b_bytes, As + (A_ELEMS + nb * B_ELEMS) * 2, wave, vob, (uint32_t)ldb);
+    // LDS byte addresses of the tile slots
+    const uint32_t lds_b0 = lds_addr + (uint32_t)(A_SLOTS * A_ELEMS * 2);
+    auto load_a = [&](const IterSrc<bf16_t, NB>& s, int slot, int j) __attribute__((always_inline)) {
+      issue_one<BM, A_KC>(s.a, s.a_bytes, lds_addr + (uint32_t)(slot * A_ELEMS * 2), wave, voa, (uint32_t)lda, j);
+    };
+    auto load_b = [&](const IterSrc<bf16_t, NB>& s, int slot, int n) __attribute__((always_inline)) {
+      const int nb = n / B_NI, j = n % B_NI;
+      issue_one<BN, B_KC>(s.b[nb], s.b_bytes, lds_b0 + (uint32_t)((slot * B_SET_ELEMS + nb * B_ELEMS) * 2), wave, vob,
+                          (uint32_t)ldb, j);
+    };
+    // a source with zero-length descriptors: the loads still issue (the wait counts below stay
+    // constant and the K loop free of branches) but read nothing and deliver zeros
+    auto source = [&](int it) __attribute__((always_inline)) {
+      IterSrc<bf16_t, NB> s = src(it < n_iters ? it : n_iters - 1);
+      if (it >= n_iters) s.a_bytes = s.b_bytes = 0;
+      return s;
     };
 
-    if (n_iters > 0) fetch(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
     static_assert(TM <= 4 && TN <= 4, "lane_offsets holds four tiles per operand");
     int ao[4], bo[4];
     lane_offsets<BM, A_KC, TM>(wm0, lane, ao);
     lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
-    // One wave per SIMD issues in order, so the overlap of LDS reads with MFMAs has to be in the
-    // instruction stream itself: while the MFMAs of k-step ks run, the fragments of ks+1 are read,
-    // one LDS read after each MFMA.
-    constexpr int kReads = (A_KC ? TM : 2 * TM) + NB * (B_KC ? TN : 2 * TN);
-    constexpr int kMfma = NB * TM * TN;
-    auto interleave = [&]() __attribute__((always_inline)) {
-#if defined(__HIP_DEVICE_COMPILE__)
+
+    constexpr int kLoadsB = NB * B_NI;  // loads per wave for the B tiles of one iteration
+    if (n_iters > 0) {
+      IterSrc<bf16_t, NB> s0 = source(0), s1 = source(1);
 #pragma unroll
-      for (int r = 0; r < (kReads < kMfma ? kReads : kMfma); r++) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-      }
-      if (kMfma > kReads) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
-      if (kReads > kMfma) __builtin_amdgcn_sched_group_barrier(0x100, kReads - kMfma, 0);
-#endif
-    };
-    for (int it = 0; it < n_iters; it++) {
-      const bf16_t* As = lds + (it & 1) * STAGE_ELEMS;
-      Frags f0, f1;
-      load_frags(As, ao, bo, 0, f0);
-      // issued behind the first LDS reads so that their latency is covered; the tile lands in the
-      // other stage while this one is multiplied
-      if (it + 1 < n_iters) fetch(it + 1);
-      __builtin_amdgcn_sched_barrier(0);
-      load_frags(As, ao, bo, 1, f1);
-      mma(acc, f0);
-      interleave();
-      load_frags(As, ao, bo, 2, f0);
-      mma(acc, f1);
-      interleave();
-      load_frags(As, ao, bo, 3, f1);
-      mma(acc, f0);
-      interleave();
-      mma(acc, f1);
-      __builtin_amdgcn_sched_barrier(0);
-      // the next tile must have landed, and every wave must be done reading this one
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+      for (int j = 0; j < A_NI; j++) load_a(s0, 0, j);
+#pragma unroll
+      for (int n = 0; n < kLoadsB; n++) load_b(s0, 0, n);
+#pragma unroll
+      for (int j = 0; j < A_NI; j++) load_a(s1, 1, j);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // One wave per SIMD issues in order and a tile load stalls its wave for as long as the texture
+    // addresser is busy with earlier loads (16 cycles per load and wave), so every overlap has to
+    // be in the instruction stream itself.  Per K iteration t (4 k-steps of kMfma MFMAs):
+    //   - the fragments of k-step ks+1 are read from LDS during the MFMAs of ks, one per MFMA;
+    //   - the loads of B(t+1), then of A(t+2), are spread evenly between the MFMAs;
+    //   - half-way through the last k-step all LDS reads of this iteration are done: wait until
+    //     B(t+1) has landed (A(t+2) may still be in flight: loads complete in order), barrier, and
+    //     read the first fragments of iteration t+1 under the remaining MFMAs.
+    constexpr int kLoads = kLoadsB + A_NI;
+    constexpr int kSlots = 4 * kMfma;                          // MFMA slots per iteration
+    constexpr int kLoadEvery = (kSlots - kMfma / 2) / kLoads;  // all loads issued before the barrier
+    static_assert(kLoadEvery >= 1, "more tile loads than MFMA slots");
+    static_assert(kFragLoads <= kMfma / 2, "fragment loads must fit into half a k-step");
+    static_assert(A_NI == 8, "the wait below leaves exactly the A loads of iteration t+2 outstanding");
+    Frags f[2];
+#pragma unroll
+    for (int r = 0; r < kFragLoads; r++) load_frag_n(lds, lds + A_SLOTS * A_ELEMS, ao, bo, 0, r, f[0]);
+    int a_cur = 0, b_cur = 0;  // slots of this iteration's tiles
+    for (int it = 0; it < n_iters; it++) {
+      const int a_nxt = a_cur == A_SLOTS - 1 ? 0 : a_cur + 1;   // A(t+1)
+      const int a_nn = a_nxt == A_SLOTS - 1 ? 0 : a_nxt + 1;    // A(t+2) goes here
+      const int b_nxt = b_cur ^ 1;
+      const bf16_t* As = lds + a_cur * A_ELEMS;
+      const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + b_cur * B_SET_ELEMS;
+      const bf16_t* An = lds + a_nxt * A_ELEMS;
+      const bf16_t* Bn = lds + A_SLOTS * A_ELEMS + b_nxt * B_SET_ELEMS;
+      const IterSrc<bf16_t, NB> s1 = source(it + 1), s2 = source(it + 2);
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) {
+#pragma unroll
+        for (int m = 0; m < kMfma; m++) {
+          const int slot = ks * kMfma + m;
+          if (ks < 3) {
+            if (m < kFragLoads) load_frag_n(As, Bs, ao, bo, ks + 1, m, f[(ks + 1) & 1]);
+          } else {
+            if (m == kMfma / 2) {
+              // B(t+1) must have landed (the 8 loads of A(t+2) issued after it may be outstanding),
+              // and every wave must be done reading this iteration's tiles
+              asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+              __syncthreads();
+            }
+            // (after the last tile this reads stale but in-bounds LDS data that is never used)
+            if (m >= kMfma / 2 && m - kMfma / 2 < kFragLoads) load_frag_n(An, Bn, ao, bo, 0, m - kMfma / 2, f[0]);
+          }
+          if (slot % kLoadEvery == 0 && slot / kLoadEvery < kLoads) {
+            const int n = slot / kLoadEvery;
+            if (n < kLoadsB) load_b(s1, b_nxt, n);
+            else load_a(s2, a_nn, n - kLoadsB);
+          }
+          mfma_n(acc, f[ks & 1], m);
+        }
+      }
+      a_cur = a_nxt;
+      b_cur = b_nxt;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // zero-length loads of the tail
     // The accumulators live in AGPRs.  Each value is copied out right where it is needed (the
     // volatile asm pins the order); left to itself the compiler copies all 256 at the loop exit,
     // needs every arch VGPR for that and spills the loop's address registers.
