@@ -43,17 +43,73 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   st_[e] = st;
   sc[e] = (e < n_groups && c > 0) ? 1 : 0;
   __syncthreads();
+  // Launch order of the groups.  Sorted by descending row count, the heavy groups (MFMA-bound) would
+  // all run before the light ones (bound by streaming their weights from HBM), and the two
+  // resources would be used one after the other.  So the light groups (at most kLightRows rows) are
+  // spread evenly, by cumulative rows, between the heavy ones: a stable merge of two sorted lists.
+  constexpr int kLightRows = 128;
+  int rank = 0;
   if (e < n_groups) {
-    int rank = 0;
     for (int o = 0; o < n_groups; o++) {
       int co = cnt[o];
       rank += (co > c) || (co == c && o < e);
     }
     ord[rank] = e;
-    pl.order[rank] = e;
+  }
+  __syncthreads();
+  {
+    // thread e now looks at the group of sorted rank e
+    const int ge = e < n_groups ? ord[e] : 0;
+    const int ce = e < n_groups ? cnt[ge] : 0;
+    const bool heavy = e < n_groups && ce > kLightRows;
+    st_[e] = heavy ? ce : 0;  // scratch: rows of heavy groups in sorted order
+    __syncthreads();
+    int n_heavy = 0;
+    long long total = 0, before = 0;
+    for (int o = 0; o < n_groups; o++) {
+      if (st_[o] > 0) {
+        n_heavy++;
+        total += st_[o];
+        if (o < e) before += st_[o];
+      }
+    }
+    const int n_light = n_groups - n_heavy;
+    int pos = e;
+    if (e < n_groups && n_heavy > 0 && n_light > 0) {
+      if (heavy) {
+        // lights whose target (l + 0.5) / n_light * total lies before this group's first row
+        // target_l < before  <=>  (2l + 1) * total < 2 * before * n_light
+        long long lim = 2 * before * n_light;
+        int nl = (int)min((long long)n_light, lim <= total ? 0ll : (lim - total + 2 * total - 1) / (2 * total));
+        pos = e + nl;  // e heavy groups precede it in sorted order (heavy ones sort first)
+      } else {
+        const int l = e - n_heavy;
+        // heavy groups whose first row is at or before the target: before_h * 2 * n_light <= (2l+1) * total
+        int nh = 0;
+        long long acc = 0;
+        for (int o = 0; o < n_heavy; o++) {
+          nh += (2 * acc * n_light <= (2ll * l + 1) * total);
+          acc += st_[o];
+        }
+        pos = l + nh;
+      }
+    }
+    __syncthreads();
+    if (e < n_groups) {
+      sc[pos] = ge;  // scratch: merged order
+    }
+    __syncthreads();
+    if (e < n_groups) ord[e] = sc[e];
+    __syncthreads();
+  }
+  if (e < n_groups) {
+    pl.order[e] = ord[e];
     pl.counts[e] = c;
     pl.starts[e] = st;
   }
+  st_[e] = st;
+  sc[e] = (e < n_groups && c > 0) ? 1 : 0;
+  __syncthreads();
   block_scan_inclusive(sc, e);
   const int total_active = sc[1023];
   if (e < n_groups) {
@@ -66,21 +122,53 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   }
   if (e == 0 && n_active) *n_active = total_active;
   __syncthreads();
-  // row tiles, groups in descending size
+  // Row tiles, groups in descending size.  BM > 0: tiles of BM rows.  BM == 0: mixed heights -- full
+  // 256-row tiles, and the remainder r of a group cut so that little MFMA work is spent on padding:
+  // r > 192: one 256 tile; (160,192]: 128 + 64; (128,160]: 128 + 32; (96,128]: 128; (64,96]: 64 + 32;
+  // (32,64]: 64; (0,32]: 32.
   const int g = e < n_groups ? ord[e] : 0;
   const int cg = e < n_groups ? cnt[g] : 0;
-  const int nt = (cg + BM - 1) / BM;
+  int nt, h0 = 0, h1 = 0;  // heights of the (up to two) remainder tiles
+  if (BM > 0) {
+    nt = (cg + BM - 1) / BM;
+  } else {
+    const int r = cg & 255;
+    if (r > 192) h0 = 256;
+    else if (r > 160) { h0 = 128; h1 = 64; }
+    else if (r > 128) { h0 = 128; h1 = 32; }
+    else if (r > 96) h0 = 128;
+    else if (r > 64) { h0 = 64; h1 = 32; }
+    else if (r > 32) h0 = 64;
+    else if (r > 0) h0 = 32;
+    nt = (cg >> 8) + (h0 > 0) + (h1 > 0);
+  }
   sc[e] = nt;
   __syncthreads();
   block_scan_inclusive(sc, e);
   const int base = sc[e] - nt;
-  for (int i = 0; i < nt; i++) {
-    RowTile t;
-    t.group = g;
-    t.row0_in = st_[g] + i * BM;
-    t.rows = min(BM, cg - i * BM);
-    t.row0_out = offsets ? t.row0_in : g * n_rows + i * BM;
-    pl.tiles[base + i] = t;
+  if (BM > 0) {
+    for (int i = 0; i < nt; i++) {
+      RowTile t;
+      t.group = g;
+      t.row0_in = st_[g] + i * BM;
+      t.rows = min(BM, cg - i * BM);
+      t.row0_out = offsets ? t.row0_in : g * n_rows + i * BM;
+      pl.tiles[base + i] = t;
+    }
+  } else {
+    int row = 0;
+    for (int i = 0; i < nt; i++) {
+      const int full = cg >> 8;
+      const int h = i < full ? 256 : (i == full ? h0 : h1);
+      const int kind = h == 256 ? 0 : h == 128 ? 1 : h == 64 ? 2 : 3;
+      RowTile t;
+      t.group = g;
+      t.row0_in = st_[g] + row;
+      t.rows = min(h, cg - row) | (kind << 16);
+      t.row0_out = offsets ? t.row0_in : g * n_rows + row;
+      pl.tiles[base + i] = t;
+      row += h;
+    }
   }
   if (e == 1023) *pl.n_tiles = sc[1023];
 }
@@ -123,24 +211,13 @@ template <> __device__ __forceinline__ float sigmoidf_<bf16_t>(float z) {
 }
 
 // --------------------------------------------------------------------- row-tiled GEMM kernel
+// CoreSet::tile<KIND> is the tile core of a tile kind; kinds differ in height only (same BN, BK), so
+// one launch serves full tiles and the short tiles of ragged groups.
 template <class Core, int NB, int EPI, bool B_KC>
-__global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
+__device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t, int nt, char* smem) {
   typedef typename Core::T T;
-  extern __shared__ __align__(16) char smem[];
-  constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
-  const int ntn = (p.N + BN - 1) / BN;
-  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
-  RowTile t;
-  if (p.tiles) {
-    if (mt >= *p.n_tiles) return;
-    t = p.tiles[mt];
-  } else {
-    t.group = 0;
-    t.row0_in = mt * BM;
-    if (t.row0_in >= p.n_rows) return;
-    t.rows = min(BM, p.n_rows - t.row0_in);
-    t.row0_out = t.row0_in;
-  }
+  constexpr int BN = Core::BN, BK = Core::BK;
+  const int rows = tile_rows(t);
   const int n0 = nt * BN;
   const int n_valid = min(BN, p.N - n0);
   const int a_row0 = p.a_rows_out ? t.row0_out : t.row0_in;
@@ -156,7 +233,7 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
     if (NB == 2) s.b[NB - 1] = (const T*)p.Bdual + boff;
     s.k_left = p.K - k0;
     const int64_t es = sizeof(T);
-    const int64_t ab = ((int64_t)(t.rows - 1) * p.lda + (p.K - k0)) * es;
+    const int64_t ab = ((int64_t)(rows - 1) * p.lda + (p.K - k0)) * es;
     const int64_t bb = B_KC ? ((int64_t)(n_valid - 1) * p.ldb + (p.K - k0)) * es
                             : ((int64_t)(p.K - k0 - 1) * p.ldb + (p.N - n0)) * es;
     s.a_bytes = clip_u32(ab);
@@ -165,7 +242,7 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
   };
   const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
   auto epi = [&](int m, int n, const float (&v)[NB][4]) __attribute__((always_inline)) {
-    if (m >= t.rows || n >= n_valid) return;
+    if (m >= rows || n >= n_valid) return;
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
     if (EPI == EPI_STORE) {
       store4<T>((T*)p.out[0] + off, v[0]);
@@ -190,7 +267,36 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
       store4<T>((T*)p.out[1] + off, du);
     }
   };
-  Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, t.rows, n_valid, epi);
+  Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, rows, n_valid, epi);
+}
+
+template <class CoreSet, int NB, int EPI, bool B_KC>
+__global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
+  extern __shared__ __align__(16) char smem[];
+  typedef typename CoreSet::template tile<0> Core0;
+  const int ntn = (p.N + Core0::BN - 1) / Core0::BN;
+  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  RowTile t;
+  if (p.tiles) {
+    if (mt >= *p.n_tiles) return;
+    t = p.tiles[mt];
+  } else {
+    t.group = 0;
+    t.row0_in = mt * Core0::BM;
+    if (t.row0_in >= p.n_rows) return;
+    t.rows = min(Core0::BM, p.n_rows - t.row0_in);
+    t.row0_out = t.row0_in;
+  }
+  if (CoreSet::kKinds == 1) {
+    row_gemm_tile<Core0, NB, EPI, B_KC>(p, t, nt, smem);
+  } else {
+    switch (tile_kind(t)) {  // uniform over the block
+      case 0: row_gemm_tile<Core0, NB, EPI, B_KC>(p, t, nt, smem); break;
+      case 1: row_gemm_tile<typename CoreSet::template tile<1>, NB, EPI, B_KC>(p, t, nt, smem); break;
+      case 2: row_gemm_tile<typename CoreSet::template tile<2>, NB, EPI, B_KC>(p, t, nt, smem); break;
+      default: row_gemm_tile<typename CoreSet::template tile<3>, NB, EPI, B_KC>(p, t, nt, smem); break;
+    }
+  }
 }
 
 // ------------------------------------------------------------------- weight-gradient kernel
@@ -249,6 +355,18 @@ template <> struct Cores<PATH_BF16_DMA> {
   template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 2>;
 };
 
+// The tile cores a row-tiled GEMM launch may use: one for the fp32 and the general bf16 path, four
+// heights (256, 128, 64, 32 rows) for the DMA path so that ragged groups waste little MFMA work.
+template <int PATH, int NB, bool B_KC> struct RowCores {
+  static constexpr int kKinds = 1;
+  template <int KIND> using tile = typename Cores<PATH>::template core<NB, true, B_KC>;
+};
+template <int NB, bool B_KC> struct RowCores<PATH_BF16_DMA, NB, B_KC> {
+  static constexpr int kKinds = 4;
+  template <int KIND>
+  using tile = MfmaDmaCore<(256 >> KIND), 256 / NB, NB, true, B_KC, (KIND <= 1 ? 2 : 1), (KIND <= 1 ? 2 : 4)>;
+};
+
 static int pick_path(const moe_shape_t* s) {
   if (s->dtype == MOE_F32) return PATH_F32;
   return (s->d % 64 == 0 && s->d_ff % 64 == 0) ? PATH_BF16_DMA : PATH_BF16;
@@ -259,16 +377,21 @@ static int path_bm(int path) {
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// upper bound of the row tiles the plan kernel may emit (BM == 0: mixed heights, at most two
+// remainder tiles per group)
 static int max_row_tiles(int n_groups, int n_rows, bool shared, int BM) {
+  if (BM == 0) return shared ? n_groups * (n_rows / 256 + 2) : n_rows / 256 + 2 * n_groups;
   return shared ? n_groups * ceil_div(n_rows, BM) : ceil_div(n_rows, BM) + n_groups;
 }
+template <int PATH> constexpr int plan_bm() { return PATH == PATH_BF16_DMA ? 0 : Cores<PATH>::BM; }
 
-template <class Core, int NB, int EPI, bool B_KC>
+template <class CoreSet, int NB, int EPI, bool B_KC>
 static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipStream_t st) {
+  typedef typename CoreSet::template tile<0> Core;
   const int ntn = ceil_div(p.N, Core::BN);
   const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, Core::BM);
   if (n_mt == 0 || ntn == 0) return;
-  auto kern = row_gemm_kernel<Core, NB, EPI, B_KC>;
+  auto kern = row_gemm_kernel<CoreSet, NB, EPI, B_KC>;
   static bool attr_done = false;
   if (!attr_done && Core::LDS_BYTES > 48 * 1024) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
@@ -304,11 +427,11 @@ template <int PATH>
 static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   typedef Cores<PATH> C;
   const bool shared = a.offsets == nullptr;
-  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
+  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, plan_bm<PATH>());
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
   {
     ProfScope prof("plan_kernel", st);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, plan_bm<PATH>(), pl,
                        (int32_t*)nullptr, (int32_t*)nullptr);
   }
   // F4: dual GEMM with the SwiGLU epilogue
@@ -318,7 +441,7 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   p.A[0] = a.Xin; p.lda = a.d; p.a_seg = 0; p.a_rows_out = 0;
   p.B[0] = a.Wg; p.Bdual = a.Wu; p.ldb = a.F; p.b_group = (int64_t)a.d * a.F; p.b_seg = 0;
   p.out[0] = a.G; p.out[1] = a.U; p.out[2] = a.H; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<typename C::template core<2, true, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
+  launch_row<RowCores<PATH, 2, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
   // F5: Yout = H Wd (shared mode: summed over groups through K segments)
   RowGemm q = {};
   q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 1;
@@ -331,7 +454,7 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   } else {
     q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.F * a.d;
   }
-  launch_row<typename C::template core<1, true, false>, 1, EPI_STORE, false>("gemm_fwd_down", q, max_tiles, st);
+  launch_row<RowCores<PATH, 1, false>, 1, EPI_STORE, false>("gemm_fwd_down", q, max_tiles, st);
 }
 
 struct BwdArgs {
@@ -350,14 +473,14 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   typedef Cores<PATH> C;
   const bool shared = a.offsets == nullptr;
   const size_t es = PATH == PATH_F32 ? 4 : 2;
-  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, C::BM);
+  const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, plan_bm<PATH>());
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
   const size_t act_rows = (size_t)(shared ? a.n_groups : 1) * a.n_rows;
   char* dG = (char*)a.ws + a.plan_sz;
   char* dU = dG + align_up(act_rows * a.F * es, 256);
   {
     ProfScope prof("plan_kernel", st);
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, C::BM, pl,
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, plan_bm<PATH>(), pl,
                        a.active_ids, a.n_active);
   }
   // B2a: dH = dYin Wd^T, epilogue turns it into dG, dU
@@ -367,7 +490,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   p.A[0] = a.dYin; p.lda = a.d; p.a_rows_out = 0;
   p.B[0] = a.Wd; p.ldb = a.d; p.b_group = (int64_t)a.F * a.d;
   p.in[0] = a.G; p.in[1] = a.U; p.out[0] = dG; p.out[1] = dU; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<typename C::template core<1, true, true>, 1, EPI_SWIGLU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
+  launch_row<RowCores<PATH, 1, true>, 1, EPI_SWIGLU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
   // B2b: dXin = dG Wg^T + dU Wu^T
   RowGemm q = {};
   q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 2;
@@ -380,7 +503,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   } else {
     q.tiles = pl.tiles; q.n_tiles = pl.n_tiles; q.n_segs = 1; q.b_group = (int64_t)a.d * a.F;
   }
-  launch_row<typename C::template core<1, true, true>, 1, EPI_STORE, true>("gemm_bwd_dx", q, max_tiles, st);
+  launch_row<RowCores<PATH, 1, true>, 1, EPI_STORE, true>("gemm_bwd_dx", q, max_tiles, st);
   // B3: weight gradients, compacted to active groups, largest group first
   WGemm w = {};
   w.order = pl.order; w.slot_of = pl.slot_of; w.counts = pl.counts; w.starts = pl.starts; w.n_rows = a.n_rows;
@@ -400,7 +523,8 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
 
 static size_t plan_size_for(const moe_shape_t* s, int n_groups, int n_rows, bool shared) {
   // sized for the smallest row tile of any path, so the query does not depend on the path taken
-  return align_up(plan_bytes(n_groups, max_row_tiles(n_groups, n_rows, shared, 64) + 1), 256);
+  const int bound = max_row_tiles(n_groups, n_rows, shared, 64) + max_row_tiles(n_groups, n_rows, shared, 0);
+  return align_up(plan_bytes(n_groups, bound + 1), 256);
 }
 
 static int check_expert_args(const moe_shape_t* s, int n_groups, int n_rows, const char* who) {

@@ -307,7 +307,8 @@ struct MfmaDmaCore {
   static constexpr int A_NI = BM / 32, B_NI = BN / 32;  // wave-wide loads per wave and tile
   static_assert(WM * WN == 4, "four wavefronts per block");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
-  static_assert(BM % 128 == 0 && BN % 128 == 0, "swizzle of row-contiguous tiles needs >= 16 pieces per k row");
+  static_assert((A_KC || BM % 128 == 0) && (B_KC || BN % 128 == 0),
+                "swizzle of row-contiguous tiles needs >= 16 pieces per k row");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
   typedef __attribute__((address_space(3))) void* lds_vptr;
 
@@ -491,11 +492,9 @@ struct MfmaDmaCore {
     //     B(t+1) has landed (A(t+2) may still be in flight: loads complete in order), barrier, and
     //     read the first fragments of iteration t+1 under the remaining MFMAs.
     constexpr int kLoads = kLoadsB + A_NI;
-    constexpr int kSlots = 4 * kMfma;                          // MFMA slots per iteration
-    constexpr int kLoadEvery = (kSlots - kMfma / 2) / kLoads;  // all loads issued before the barrier
-    static_assert(kLoadEvery >= 1, "more tile loads than MFMA slots");
-    static_assert(kFragLoads <= kMfma / 2, "fragment loads must fit into half a k-step");
-    static_assert(A_NI == 8, "the wait below leaves exactly the A loads of iteration t+2 outstanding");
+    constexpr int kHalf = kMfma / 2;                 // MFMAs of the last k-step before the barrier
+    constexpr int kSlots = 3 * kMfma + kHalf;        // MFMA slots before the barrier: all loads issue here
+    constexpr int kLate = kMfma - kHalf;             // MFMAs after the barrier
     Frags f[2];
 #pragma unroll
     for (int r = 0; r < kFragLoads; r++) load_frag_n(lds, lds + A_SLOTS * A_ELEMS, ao, bo, 0, r, f[0]);
@@ -513,23 +512,33 @@ struct MfmaDmaCore {
       for (int ks = 0; ks < 4; ks++) {
 #pragma unroll
         for (int m = 0; m < kMfma; m++) {
-          const int slot = ks * kMfma + m;
           if (ks < 3) {
-            if (m < kFragLoads) load_frag_n(As, Bs, ao, bo, ks + 1, m, f[(ks + 1) & 1]);
+            // fragment loads of k-step ks+1, spread over the MFMAs of ks
+#pragma unroll
+            for (int r = m * kFragLoads / kMfma; r < (m + 1) * kFragLoads / kMfma; r++)
+              load_frag_n(As, Bs, ao, bo, ks + 1, r, f[(ks + 1) & 1]);
           } else {
-            if (m == kMfma / 2) {
-              // B(t+1) must have landed (the 8 loads of A(t+2) issued after it may be outstanding),
-              // and every wave must be done reading this iteration's tiles
-              asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            if (m == kHalf) {
+              // B(t+1) must have landed (the A_NI loads of A(t+2) issued after it may still be
+              // outstanding), and every wave must be done reading this iteration's tiles
+              asm volatile("s_waitcnt vmcnt(%0)" ::"n"(A_NI) : "memory");
               __syncthreads();
             }
+            // first fragments of iteration t+1 under the remaining MFMAs
             // (after the last tile this reads stale but in-bounds LDS data that is never used)
-            if (m >= kMfma / 2 && m - kMfma / 2 < kFragLoads) load_frag_n(An, Bn, ao, bo, 0, m - kMfma / 2, f[0]);
+            if (m >= kHalf) {
+#pragma unroll
+              for (int r = (m - kHalf) * kFragLoads / kLate; r < (m - kHalf + 1) * kFragLoads / kLate; r++)
+                load_frag_n(An, Bn, ao, bo, 0, r, f[0]);
+            }
           }
-          if (slot % kLoadEvery == 0 && slot / kLoadEvery < kLoads) {
-            const int n = slot / kLoadEvery;
-            if (n < kLoadsB) load_b(s1, b_nxt, n);
-            else load_a(s2, a_nn, n - kLoadsB);
+          const int slot = ks * kMfma + m;
+          if (slot < kSlots) {
+#pragma unroll
+            for (int n = slot * kLoads / kSlots; n < (slot + 1) * kLoads / kSlots; n++) {
+              if (n < kLoadsB) load_b(s1, b_nxt, n);
+              else load_a(s2, a_nn, n - kLoadsB);
+            }
           }
           mfma_n(acc, f[ks & 1], m);
         }
@@ -541,7 +550,21 @@ struct MfmaDmaCore {
     // The accumulators live in AGPRs.  Each value is copied out right where it is needed (the
     // volatile asm pins the order); left to itself the compiler copies all 256 at the loop exit,
     // needs every arch VGPR for that and spills the loop's address registers.
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");  // MFMA results must have retired
+    // The MFMAs above are opaque to the compiler's hazard recogniser, so the wait between the last
+    // MFMA (8 passes of 4 cycles, plus write-back) and the first read of any accumulator is
+    // explicit: 6 x 16 idle cycles, attached to the accumulator of the last MFMA.  The empty
+    // statements make every other accumulator depend on a point after that wait (volatile asm
+    // statements keep their order), so no compiler-generated accumulator copy can move above it.
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15"
+                 : "+a"(acc[NB - 1][TM - 1][TN - 1])
+                 :
+                 : "memory");
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
 #pragma unroll
     for (int i = 0; i < TM; i++)
 #pragma unroll

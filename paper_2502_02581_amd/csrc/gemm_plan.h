@@ -9,9 +9,14 @@ namespace moe {
 struct RowTile {
   int32_t group;     // expert that owns the rows
   int32_t row0_in;   // first row in the [n_rows, .] input/output of the call
-  int32_t rows;      // valid rows (<= BM)
+  int32_t rows;      // valid rows (<= tile height) in the low 16 bits, tile kind in the high 16 bits
   int32_t row0_out;  // first row in the per-group saved activations (differs in shared mode)
 };
+
+__host__ __device__ inline int tile_rows(const RowTile& t) { return t.rows & 0xffff; }
+__host__ __device__ inline int tile_kind(const RowTile& t) { return t.rows >> 16; }
+// heights of the tile kinds of the mixed-height plan (kind 0 is the full tile)
+__host__ __device__ inline int kind_height(int kind) { return 256 >> kind; }
 
 // Device-built plan, laid out in the workspace.
 struct Plan {
