@@ -88,6 +88,27 @@ def cpu_baseline(cfg, inp, weights, budget_tokens):
             "sample": f"first {n} of {cfg.T} tokens of the same workload, fwd+bwd, fp64 numpy oracle, {dt:.1f} s"}
 
 
+def verify(cfg, inp, weights, hp):
+    """Sampled check of the timed path against the oracle; a wrong result must never be timed."""
+    import numpy as np
+    from oracle import moe_oracle as orc
+
+    W = {k: LazyExperts(v) for k, v in weights.items()}
+    idx = hp.b["topk_idx"].cpu().numpy()
+    w = hp.b["topk_w"].cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for t in (0, cfg.T // 2, cfg.T - 1):
+        y, dx, _ = orc.token_fwd_bwd(inp["X"][t].double().numpy(), idx[t], w[t], inp["dY"][t].double().numpy(),
+                                     W["Wg"], W["Wu"], W["Wd"], W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
+        for got, ref in ((hp.b["Y"][t], y), (hp.b["dX"][t], dx)):
+            err = float(np.abs(got.double().cpu().numpy() - ref).max() / np.abs(ref).max())
+            worst = max(worst, err)
+    tol = 1e-4 if cfg.dtype == "f32" else 2e-2
+    if not worst <= tol:
+        raise SystemExit(f"bench.py: the hot path disagrees with the oracle on sampled tokens (error {worst:.3e} > {tol})")
+    return worst
+
+
 CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 96, "phi": 48, "dsv3": 32, "stress": 96}
 
 
@@ -123,9 +144,10 @@ def main():
         hp.forward(g["logits"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
         hp.backward(g["dY"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
 
-    for _ in range(args.warmup):
+    for _ in range(max(1, args.warmup)):
         step()
     torch.cuda.synchronize()
+    sampled_err = verify(cfg, inp, weights, hp)
     moe.moe_profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -171,7 +193,7 @@ def main():
                    "load_share_std": round(float((counts.double() / counts.sum()).std(unbiased=False)), 5)},
         "grouped_gemm_tflops": round(gemm_tflops, 2), "grouped_gemm_frac_mfma_peak": round(gemm_tflops / peak, 4),
         "total_tflops": round(cfg.flops()["total"] / (ms_per_step * 1e-3) / 1e12, 2),
-        "roofline": roofline, "kernels": kernels,
+        "roofline": roofline, "kernels": kernels, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, weights, CPU_SAMPLE_TOKENS[cfg.name])

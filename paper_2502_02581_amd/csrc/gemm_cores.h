@@ -352,7 +352,12 @@ struct MfmaDmaCore {
     rsrc[2] = __builtin_amdgcn_readfirstlane((int)(bytes > skip ? bytes - skip : 0u));
     rsrc[3] = 0x00020000;
     const uint32_t dst = lds_tile_addr + (uint32_t)(j * 4 + wave) * 1024u;
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+    // The compiler's hazard recogniser does not look inside inline assembly.  Two hazards of this
+    // hardware generation apply here: an SGPR written by a VALU instruction (v_readfirstlane, which
+    // the compiler uses to make descriptor words uniform) must not be read by a vector memory
+    // instruction within 5 wait states, and M0 must not be read by an LDS-DMA load in the wait
+    // state after its write.  The s_nop 4 covers both (the operands are set up before the statement).
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(dst), "v"(voff), "s"(rsrc)
                  : "memory");

@@ -88,6 +88,11 @@ LAYER_CASES = [
     (small_cfg("bf16-many-empty", T=40, d=64, E=64, k=2, d_ff=64, dtype="bf16", zipf_s=2.5), True),
     (small_cfg("bf16-E1", T=200, d=64, E=1, k=1, d_ff=128, dtype="bf16"), True),
     (small_cfg("bf16-kE", T=96, d=64, E=4, k=4, d_ff=64, dtype="bf16"), True),
+    # full 256-row tiles with several K iterations, ragged remainders of every tile height
+    (small_cfg("bf16-big-tiles", T=1500, d=512, E=3, k=2, d_ff=384, dtype="bf16", zipf_s=0.5), True),
+    (small_cfg("bf16-big-shared", T=700, d=256, E=2, k=1, d_ff=256, dtype="bf16", zipf_s=0.3, n_shared=1,
+               d_ff_shared=320), True),
+    (small_cfg("bf16-heights", T=620, d=128, E=12, k=3, d_ff=192, dtype="bf16", zipf_s=1.3, gate="sigmoid"), False),
     (small_cfg("bf16-stress", T=512, d=128, E=24, k=4, d_ff=96, dtype="bf16", routing="stress", zipf_s=1.5,
                ), True),
 ]
