@@ -174,28 +174,45 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 }
 
 // ------------------------------------------------------------------------------- epilogues
-template <typename T> __device__ __forceinline__ void store4(T* p, const float (&v)[4]);
-template <> __device__ __forceinline__ void store4<float>(float* p, const float (&v)[4]) {
-  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
-}
-template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const float (&v)[4]) {
-  uint2 w;
-  w.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-  w.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-  *reinterpret_cast<uint2*>(p) = w;
-}
-template <typename T> __device__ __forceinline__ void load4(const T* p, float (&v)[4]);
-template <> __device__ __forceinline__ void load4<float>(const float* p, float (&v)[4]) {
-  float4 f = *reinterpret_cast<const float4*>(p);
-  v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
-}
-template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
-  uint2 w = *reinterpret_cast<const uint2*>(p);
-  v[0] = __uint_as_float(w.x << 16);
-  v[1] = __uint_as_float(w.x & 0xffff0000u);
-  v[2] = __uint_as_float(w.y << 16);
-  v[3] = __uint_as_float(w.y & 0xffff0000u);
-}
+// W consecutive elements (W = 4 or 8) narrowed from / widened to fp32, one or two 16-byte accesses
+template <typename T, int W> struct Pack;
+template <int W> struct Pack<float, W> {
+  __device__ static __forceinline__ void store(float* p, const float (&v)[W]) {
+#pragma unroll
+    for (int i = 0; i < W; i += 4) *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
+  }
+  __device__ static __forceinline__ void load(const float* p, float (&v)[W]) {
+#pragma unroll
+    for (int i = 0; i < W; i += 4) {
+      float4 f = *reinterpret_cast<const float4*>(p + i);
+      v[i] = f.x; v[i + 1] = f.y; v[i + 2] = f.z; v[i + 3] = f.w;
+    }
+  }
+};
+template <int W> struct Pack<bf16_t, W> {
+  __device__ static __forceinline__ void store(bf16_t* p, const float (&v)[W]) {
+    uint32_t w[W / 2];
+#pragma unroll
+    for (int i = 0; i < W / 2; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    if (W == 4) *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+    else *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[W / 2 - 2], w[W / 2 - 1]);
+  }
+  __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[W]) {
+    uint32_t w[W / 2];
+    if (W == 4) {
+      uint2 t = *reinterpret_cast<const uint2*>(p);
+      w[0] = t.x; w[1] = t.y;
+    } else {
+      uint4 t = *reinterpret_cast<const uint4*>(p);
+      w[0] = t.x; w[1] = t.y; w[W / 2 - 2] = t.z; w[W / 2 - 1] = t.w;
+    }
+#pragma unroll
+    for (int i = 0; i < W / 2; i++) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
 
 enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2 };
 
@@ -241,30 +258,32 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
     return s;
   };
   const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
-  auto epi = [&](int m, int n, const float (&v)[NB][4]) __attribute__((always_inline)) {
+  // W consecutive columns of one row (W = 4 from the fp32 and general cores, 8 from the DMA core)
+  auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) {
+    constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= rows || n >= n_valid) return;
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
     if (EPI == EPI_STORE) {
-      store4<T>((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
     } else if (EPI == EPI_SWIGLU_FWD) {
-      float h[4];
+      float h[W];
 #pragma unroll
-      for (int q = 0; q < 4; q++) h[q] = v[0][q] * sigmoidf_<T>(v[0][q]) * v[NB - 1][q];
-      store4<T>((T*)p.out[0] + off, v[0]);
-      store4<T>((T*)p.out[1] + off, v[NB - 1]);
-      store4<T>((T*)p.out[2] + off, h);
+      for (int q = 0; q < W; q++) h[q] = v[0][q] * sigmoidf_<T>(v[0][q]) * v[NB - 1][q];
+      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store((T*)p.out[1] + off, v[NB - 1]);
+      Pack<T, W>::store((T*)p.out[2] + off, h);
     } else {
-      float g[4], u[4], dg[4], du[4];
-      load4<T>((const T*)p.in[0] + off, g);
-      load4<T>((const T*)p.in[1] + off, u);
+      float g[W], u[W], dg[W], du[W];
+      Pack<T, W>::load((const T*)p.in[0] + off, g);
+      Pack<T, W>::load((const T*)p.in[1] + off, u);
 #pragma unroll
-      for (int q = 0; q < 4; q++) {
+      for (int q = 0; q < W; q++) {
         const float s = sigmoidf_<T>(g[q]);
         du[q] = v[0][q] * g[q] * s;
         dg[q] = v[0][q] * u[q] * s * (1.f + g[q] * (1.f - s));
       }
-      store4<T>((T*)p.out[0] + off, dg);
-      store4<T>((T*)p.out[1] + off, du);
+      Pack<T, W>::store((T*)p.out[0] + off, dg);
+      Pack<T, W>::store((T*)p.out[1] + off, du);
     }
   };
   Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, rows, n_valid, epi);
@@ -307,7 +326,7 @@ __global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
   const int g = p.order ? p.order[blockIdx.y] : blockIdx.y;
   const int K = p.counts ? p.counts[g] : p.n_rows;
-  if (K <= 0) return;
+  if (K <= 0 || K < p.k_min || K > p.k_max) return;
   const int start = p.starts ? p.starts[g] : 0;
   const int slot = p.slot_of ? p.slot_of[g] : g;
   const int ntn = (p.N + BN - 1) / BN;
@@ -327,11 +346,12 @@ __global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
     s.b_bytes = clip_u32(((int64_t)(K - k0 - 1) * p.ldb + (p.N - n0)) * es);
     return s;
   };
-  auto epi = [&](int m, int n, const float (&v)[NB][4]) __attribute__((always_inline)) {
+  auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) {
+    constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= m_valid || n >= n_valid) return;
     const int64_t off = (int64_t)slot * p.c_slot + (int64_t)(m0 + m) * p.N + n0 + n;
-    store4<T>((T*)p.C[0] + off, v[0]);
-    if (NB == 2) store4<T>((T*)p.C[1] + off, v[NB - 1]);
+    Pack<T, W>::store((T*)p.C[0] + off, v[0]);
+    if (NB == 2) Pack<T, W>::store((T*)p.C[1] + off, v[NB - 1]);
   };
   Core::run(smem, (K + BK - 1) / BK, src, p.lda, p.ldb, m_valid, n_valid, epi);
 }
@@ -353,7 +373,10 @@ template <> struct Cores<PATH_BF16_DMA> {
   static constexpr int BM = 256, BN = 256;
   // one block computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each of the two products)
   template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 2>;
+  // weight gradients of groups with few rows: 128 x 128 outputs per product, one tile slot
+  template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, false>;
 };
+constexpr int kLightGroupRows = 128;  // groups up to this many rows take the light dW kernel
 
 // The tile cores a row-tiled GEMM launch may use: one for the fp32 and the general bf16 path, four
 // heights (256, 128, 64, 32 rows) for the DMA path so that ragged groups waste little MFMA work.
@@ -511,13 +534,30 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   w.A = a.H; w.lda = a.F; w.a_per_group = shared;
   w.B[0] = a.dYin; w.ldb = a.d; w.b_per_group = 0;
   w.C[0] = a.dWd; w.c_slot = (int64_t)a.F * a.d;
-  launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
   WGemm v = {};
   v.order = pl.order; v.slot_of = pl.slot_of; v.counts = pl.counts; v.starts = pl.starts; v.n_rows = a.n_rows;
   v.M = a.d; v.N = a.F;
   v.A = a.Xin; v.lda = a.d; v.a_per_group = 0;
   v.B[0] = dG; v.B[1] = dU; v.ldb = a.F; v.b_per_group = shared;
   v.C[0] = a.dWg; v.C[1] = a.dWu; v.c_slot = (int64_t)a.d * a.F;
+  w.k_min = v.k_min = 1;
+  w.k_max = v.k_max = 0x7fffffff;
+  if constexpr (PATH == PATH_BF16_DMA) {
+    // groups with few rows are bound by writing their gradient, not by MFMA work: they go to a
+    // kernel that keeps several blocks per CU in flight
+    if (!shared) {
+      w.k_min = v.k_min = kLightGroupRows + 1;
+      WGemm wl_ = w, vl_ = v;
+      wl_.k_min = vl_.k_min = 1;
+      wl_.k_max = vl_.k_max = kLightGroupRows;
+      launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
+      launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
+      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dwd", wl_, a.n_groups, st);
+      launch_w<typename C::template core_light<2>, 2>("gemm_bwd_dwgu", vl_, a.n_groups, st);
+      return;
+    }
+  }
+  launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
   launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
 }
 

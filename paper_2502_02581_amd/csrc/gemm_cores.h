@@ -291,7 +291,7 @@ struct MfmaCore {
 //  K-contiguous operand [rows][64]: 16-byte piece c of a row sits at position c ^ ((row/2)%8).
 //  row-contiguous operand [64 k][ROWS]: piece c (8 columns) of k-row k sits at position
 //    c ^ (4*(k%4)), which spreads the four k rows of a transposing read over all banks.
-template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2>
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, bool RING = true>
 struct MfmaDmaCore {
   typedef bf16_t T;
   static constexpr int BM = BM_, BN = BN_, BK = 64, NT = 256;
@@ -301,9 +301,15 @@ struct MfmaDmaCore {
   // LDS: a ring of three A tiles and a ring of two B tile sets.  The A tile of iteration t+2 is
   // requested while the B tiles of t+1 are still landing, so the memory pipeline never runs dry
   // at the per-iteration barrier.
-  static constexpr int A_SLOTS = 3, B_SLOTS = 2;
+  // RING = false is the variant for groups with very few rows of K (weight gradients of experts
+  // that received a handful of tokens): one tile slot, no software pipeline, small enough in LDS
+  // and registers for several blocks per CU, which is what hides latency when a block's life is
+  // one K iteration and an epilogue.
+  static constexpr int A_SLOTS = RING ? 3 : 1, B_SLOTS = RING ? 2 : 1;
   static constexpr int B_SET_ELEMS = NB * B_ELEMS;
-  static constexpr int LDS_BYTES = (A_SLOTS * A_ELEMS + B_SLOTS * B_SET_ELEMS) * 2;
+  static constexpr int TILE_BYTES = (A_SLOTS * A_ELEMS + B_SLOTS * B_SET_ELEMS) * 2;
+  static constexpr int STAGING_BYTES = 4 * NB * 32 * ((BN_ / WN_) + 4) * 4;  // epilogue, see run()
+  static constexpr int LDS_BYTES = TILE_BYTES > STAGING_BYTES ? TILE_BYTES : STAGING_BYTES;
   static constexpr int A_NI = BM / 32, B_NI = BN / 32;  // wave-wide loads per wave and tile
   static_assert(WM * WN == 4, "four wavefronts per block");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
@@ -448,6 +454,16 @@ struct MfmaDmaCore {
         for (int j = 0; j < TN; j++)
 #pragma unroll
           for (int r = 0; r < 16; r++) acc[nb][i][j][r] = 0.f;
+    // Pin the zeroing here.  Left alone, the compiler may materialise an accumulator's zeros right
+    // in front of its first MFMA; that MFMA is inline assembly, so nobody would insert the wait
+    // states a VALU write to an accumulator register needs before an MFMA reads it.
+#pragma unroll
+    for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
+    asm volatile("s_nop 7" ::: "memory");
 
     const uint32_t voa = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda);
     const uint32_t vob = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb);
@@ -476,6 +492,28 @@ struct MfmaDmaCore {
     lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
 
     constexpr int kLoadsB = NB * B_NI;  // loads per wave for the B tiles of one iteration
+    if constexpr (!RING) {
+      // single slot: load a tile, wait, multiply; k-steps beyond the rows of K are skipped
+      for (int it = 0; it < n_iters; it++) {
+        const IterSrc<bf16_t, NB> s0 = source(it);
+        if (it > 0) __syncthreads();
+#pragma unroll
+        for (int j = 0; j < A_NI; j++) load_a(s0, 0, j);
+#pragma unroll
+        for (int n = 0; n < kLoadsB; n++) load_b(s0, 0, n);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+          if (ks * 16 >= s0.k_left) continue;  // uniform: the remaining k rows of the tile are zero
+          Frags f;
+#pragma unroll
+          for (int r = 0; r < kFragLoads; r++) load_frag_n(lds, lds + A_SLOTS * A_ELEMS, ao, bo, ks, r, f);
+#pragma unroll
+          for (int m = 0; m < kMfma; m++) mfma_n(acc, f, m);
+        }
+      }
+    } else {
     if (n_iters > 0) {
       IterSrc<bf16_t, NB> s0 = source(0), s1 = source(1);
 #pragma unroll
@@ -551,6 +589,7 @@ struct MfmaDmaCore {
       a_cur = a_nxt;
       b_cur = b_nxt;
     }
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // zero-length loads of the tail
     // The accumulators live in AGPRs.  Each value is copied out right where it is needed (the
     // volatile asm pins the order); left to itself the compiler copies all 256 at the loop exit,
@@ -570,20 +609,48 @@ struct MfmaDmaCore {
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
+    // Epilogue through LDS.  In the MFMA result layout a lane owns four consecutive columns of one
+    // row, which would make every global store a scatter of 8-byte pieces over 32 rows.  Each wave
+    // therefore passes its 32-row blocks through a private LDS region (fp32, rows padded by 16
+    // bytes: conflict-free 16-byte writes and reads) and picks them up again with eight
+    // consecutive columns per lane, so that the epilogue stores whole 128-byte lines.
+    __syncthreads();  // every wave is done with the tile slots (stale fragment reads included)
+    constexpr int CW = TN * 32;          // columns of the wave tile (per product)
+    constexpr int RS = CW + 4;           // row stride of the staging region, in floats
+    constexpr int LPR = CW / 8;          // lanes per row when reading back
+    constexpr int RPP = 64 / LPR;        // rows per read pass
+    static_assert(4 * NB * 32 * RS * 4 <= LDS_BYTES, "staging regions of the four waves fit into LDS");
+    static_assert(4 * NB * 32 * RS * 4 == STAGING_BYTES, "STAGING_BYTES matches the staging layout");
+    float* stage = reinterpret_cast<float*>(smem) + wave * (NB * 32 * RS);
 #pragma unroll
-    for (int i = 0; i < TM; i++)
+    for (int i = 0; i < TM; i++) {
 #pragma unroll
-      for (int j = 0; j < TN; j++)
+      for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          float vals[NB][4];
+        for (int j = 0; j < TN; j++)
 #pragma unroll
-          for (int nb = 0; nb < NB; nb++)
+          for (int g = 0; g < 4; g++) {
+            float4 v;
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.x) : "a"(acc[nb][i][j][4 * g + 0]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.y) : "a"(acc[nb][i][j][4 * g + 1]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.z) : "a"(acc[nb][i][j][4 * g + 2]));
+            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.w) : "a"(acc[nb][i][j][4 * g + 3]));
+            *reinterpret_cast<float4*>(stage + (nb * 32 + (lane & 31)) * RS + j * 32 + 8 * g + 4 * (lane >> 5)) = v;
+          }
 #pragma unroll
-            for (int q = 0; q < 4; q++)
-              asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(vals[nb][q]) : "a"(acc[nb][i][j][4 * g + q]));
-          epi(wm0 + i * 32 + (lane & 31), wn0 + j * 32 + 8 * g + 4 * (lane >> 5), vals);
+      for (int pass = 0; pass < 32 / RPP; pass++) {
+        const int row = pass * RPP + lane / LPR, c0 = (lane % LPR) * 8;
+        float vals[NB][8];
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) {
+          const float4 lo = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0);
+          const float4 hi = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0 + 4);
+          vals[nb][0] = lo.x; vals[nb][1] = lo.y; vals[nb][2] = lo.z; vals[nb][3] = lo.w;
+          vals[nb][4] = hi.x; vals[nb][5] = hi.y; vals[nb][6] = hi.z; vals[nb][7] = hi.w;
         }
+        epi(wm0 + i * 32 + row, wn0 + c0, vals);
+      }
+    }
   }
 };
 

@@ -86,6 +86,7 @@ struct WGemm {
   int32_t b_per_group;
   void* C[2];
   int64_t c_slot;           // elements per slot
+  int32_t k_min, k_max;     // only groups with k_min <= rows <= k_max are processed by this launch
 };
 
 }  // namespace moe
