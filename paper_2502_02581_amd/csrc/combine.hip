@@ -5,65 +5,170 @@
 
 namespace moe {
 
-template <typename T>
+// K > 0: k known at compile time (all loops unrolled, the k gathered loads of a piece are in flight
+// together); K == 0: any k.
+template <typename T, int K>
 __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ Yp,
                                                       const int32_t* __restrict__ row_of,
                                                       const float* __restrict__ topk_w,
-                                                      const T* Yadd, T* Y, int d, int k) {
+                                                      const T* Yadd, T* Y, int d, int k_rt) {
   constexpr int N = Vec16<T>::N;
+  constexpr int KM = K > 0 ? K : 1;
+  const int k = K > 0 ? K : k_rt;
   const int t = blockIdx.x;
   const int vec_per_row = d / N;
-  for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
-    float acc[N];
-    if (Yadd) {
-      Vec16<T>::load(Yadd + (size_t)t * d + c * N, acc);
-    } else {
+  if (K > 0) {
+    const T* src[KM];
+    float w[KM];
 #pragma unroll
-      for (int i = 0; i < N; i++) acc[i] = 0.f;
+    for (int j = 0; j < KM; j++) {
+      src[j] = Yp + (size_t)row_of[(size_t)t * k + j] * d;
+      w[j] = topk_w ? topk_w[(size_t)t * k + j] : 1.f;
     }
-    for (int j = 0; j < k; j++) {
-      const int r = row_of[(size_t)t * k + j];
-      const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.f;
-      float v[N];
-      Vec16<T>::load(Yp + (size_t)r * d + c * N, v);
+    for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+      float v[KM][N], acc[N];
 #pragma unroll
-      for (int i = 0; i < N; i++) acc[i] = fmaf(w, v[i], acc[i]);
+      for (int j = 0; j < KM; j++) Vec16<T>::load(src[j] + c * N, v[j]);
+      if (Yadd) {
+        Vec16<T>::load(Yadd + (size_t)t * d + c * N, acc);
+      } else {
+#pragma unroll
+        for (int i = 0; i < N; i++) acc[i] = 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < KM; j++)
+#pragma unroll
+        for (int i = 0; i < N; i++) acc[i] = fmaf(w[j], v[j][i], acc[i]);
+      Vec16<T>::store(Y + (size_t)t * d + c * N, acc);
     }
-    Vec16<T>::store(Y + (size_t)t * d + c * N, acc);
+  } else {
+    for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+      float acc[N];
+      if (Yadd) {
+        Vec16<T>::load(Yadd + (size_t)t * d + c * N, acc);
+      } else {
+#pragma unroll
+        for (int i = 0; i < N; i++) acc[i] = 0.f;
+      }
+      for (int j = 0; j < k; j++) {
+        const int r = row_of[(size_t)t * k + j];
+        const float w = topk_w ? topk_w[(size_t)t * k + j] : 1.f;
+        float v[N];
+        Vec16<T>::load(Yp + (size_t)r * d + c * N, v);
+#pragma unroll
+        for (int i = 0; i < N; i++) acc[i] = fmaf(w, v[i], acc[i]);
+      }
+      Vec16<T>::store(Y + (size_t)t * d + c * N, acc);
+    }
   }
 }
 
-template <typename T>
+// dYp rows and the k dot products of one token.  The partial dots stay in registers over the whole
+// row; one wave reduction per slot and one exchange through LDS per token.
+template <typename T, int K>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dY, const T* __restrict__ Yp,
                                                           const int32_t* __restrict__ row_of,
                                                           const float* __restrict__ topk_w,
                                                           T* __restrict__ dYp, float* __restrict__ dw, int d,
-                                                          int k) {
+                                                          int k_rt) {
   constexpr int N = Vec16<T>::N;
-  __shared__ float part[4];
+  constexpr int KM = K > 0 ? K : 1;
+  const int k = K > 0 ? K : k_rt;
+  __shared__ float part[4][KM > 1 ? KM : 1];
   const int t = blockIdx.x;
   const int vec_per_row = d / N;
-  for (int j = 0; j < k; j++) {
-    const int r = row_of[(size_t)t * k + j];
-    const float w = topk_w[(size_t)t * k + j];
-    float dot = 0.f;
-    for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
-      float g[N], y[N], o[N];
-      Vec16<T>::load(dY + (size_t)t * d + c * N, g);
-      Vec16<T>::load(Yp + (size_t)r * d + c * N, y);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (K > 0) {
+    size_t row[KM];
+    float w[KM], dot[KM];
 #pragma unroll
-      for (int i = 0; i < N; i++) {
-        o[i] = w * g[i];
-        dot = fmaf(g[i], y[i], dot);
-      }
-      Vec16<T>::store(dYp + (size_t)r * d + c * N, o);
+    for (int j = 0; j < KM; j++) {
+      row[j] = (size_t)row_of[(size_t)t * k + j] * d;
+      w[j] = topk_w[(size_t)t * k + j];
+      dot[j] = 0.f;
     }
-    dot = wave_sum(dot);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
+    for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+      float g[N], y[KM][N];
+      Vec16<T>::load(dY + (size_t)t * d + c * N, g);
+#pragma unroll
+      for (int j = 0; j < KM; j++) Vec16<T>::load(Yp + row[j] + c * N, y[j]);
+#pragma unroll
+      for (int j = 0; j < KM; j++) {
+        float o[N];
+#pragma unroll
+        for (int i = 0; i < N; i++) {
+          o[i] = w[j] * g[i];
+          dot[j] = fmaf(g[i], y[j][i], dot[j]);
+        }
+        Vec16<T>::store(dYp + row[j] + c * N, o);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < KM; j++) {
+      const float s = wave_sum(dot[j]);
+      if (lane == 0) part[wave][j] = s;
+    }
     __syncthreads();
-    if (threadIdx.x == 0) dw[(size_t)t * k + j] = (part[0] + part[1]) + (part[2] + part[3]);
-    __syncthreads();
+    if (threadIdx.x < KM)
+      dw[(size_t)t * k + threadIdx.x] =
+          (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+  } else {
+    for (int j = 0; j < k; j++) {
+      const size_t r = (size_t)row_of[(size_t)t * k + j] * d;
+      const float w = topk_w[(size_t)t * k + j];
+      float dot = 0.f;
+      for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+        float g[N], y[N], o[N];
+        Vec16<T>::load(dY + (size_t)t * d + c * N, g);
+        Vec16<T>::load(Yp + r + c * N, y);
+#pragma unroll
+        for (int i = 0; i < N; i++) {
+          o[i] = w * g[i];
+          dot = fmaf(g[i], y[i], dot);
+        }
+        Vec16<T>::store(dYp + r + c * N, o);
+      }
+      dot = wave_sum(dot);
+      if (lane == 0) part[wave][0] = dot;
+      __syncthreads();
+      if (threadIdx.x == 0) dw[(size_t)t * k + j] = (part[0][0] + part[1][0]) + (part[2][0] + part[3][0]);
+      __syncthreads();
+    }
   }
+}
+
+template <typename T>
+static void launch_combine(const moe_shape_t* s, const void* Yp, const int32_t* row_of, const float* topk_w,
+                           const void* Yadd, void* Y, hipStream_t st) {
+  dim3 grid(s->T), block(256);
+#define MOE_COMBINE(K)                                                                                       \
+  hipLaunchKernelGGL((combine_kernel<T, K>), grid, block, 0, st, (const T*)Yp, row_of, topk_w, (const T*)Yadd, \
+                     (T*)Y, s->d, s->k)
+  switch (s->k) {
+    case 1: MOE_COMBINE(1); break;
+    case 2: MOE_COMBINE(2); break;
+    case 4: MOE_COMBINE(4); break;
+    case 8: MOE_COMBINE(8); break;
+    default: MOE_COMBINE(0); break;
+  }
+#undef MOE_COMBINE
+}
+
+template <typename T>
+static void launch_combine_bwd(const moe_shape_t* s, const void* dY, const void* Yp, const int32_t* row_of,
+                               const float* topk_w, void* dYp, float* dw, hipStream_t st) {
+  dim3 grid(s->T), block(256);
+#define MOE_COMBINE_BWD(K)                                                                                    \
+  hipLaunchKernelGGL((combine_bwd_kernel<T, K>), grid, block, 0, st, (const T*)dY, (const T*)Yp, row_of, topk_w, \
+                     (T*)dYp, dw, s->d, s->k)
+  switch (s->k) {
+    case 1: MOE_COMBINE_BWD(1); break;
+    case 2: MOE_COMBINE_BWD(2); break;
+    case 4: MOE_COMBINE_BWD(4); break;
+    case 8: MOE_COMBINE_BWD(8); break;
+    default: MOE_COMBINE_BWD(0); break;
+  }
+#undef MOE_COMBINE_BWD
 }
 
 }  // namespace moe
@@ -84,12 +189,8 @@ extern "C" int moe_combine(const moe_shape_t* shape, const void* Yp, const int32
   }
   hipStream_t st = (hipStream_t)stream;
   ProfScope prof("combine_kernel", st);
-  if (shape->dtype == MOE_F32)
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(shape->T), dim3(256), 0, st, (const float*)Yp, row_of, topk_w,
-                       (const float*)Yadd, (float*)Y, shape->d, shape->k);
-  else
-    hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(shape->T), dim3(256), 0, st, (const bf16_t*)Yp, row_of,
-                       topk_w, (const bf16_t*)Yadd, (bf16_t*)Y, shape->d, shape->k);
+  if (shape->dtype == MOE_F32) launch_combine<float>(shape, Yp, row_of, topk_w, Yadd, Y, st);
+  else launch_combine<bf16_t>(shape, Yp, row_of, topk_w, Yadd, Y, st);
   return launch_status("moe_combine");
 }
 
@@ -109,11 +210,7 @@ extern "C" int moe_combine_bwd(const moe_shape_t* shape, const void* dY, const v
   }
   hipStream_t st = (hipStream_t)stream;
   ProfScope prof("combine_bwd_kernel", st);
-  if (shape->dtype == MOE_F32)
-    hipLaunchKernelGGL(combine_bwd_kernel<float>, dim3(shape->T), dim3(256), 0, st, (const float*)dY,
-                       (const float*)Yp, row_of, topk_w, (float*)dYp, dw, shape->d, shape->k);
-  else
-    hipLaunchKernelGGL(combine_bwd_kernel<bf16_t>, dim3(shape->T), dim3(256), 0, st, (const bf16_t*)dY,
-                       (const bf16_t*)Yp, row_of, topk_w, (bf16_t*)dYp, dw, shape->d, shape->k);
+  if (shape->dtype == MOE_F32) launch_combine_bwd<float>(shape, dY, Yp, row_of, topk_w, dYp, dw, st);
+  else launch_combine_bwd<bf16_t>(shape, dY, Yp, row_of, topk_w, dYp, dw, st);
   return launch_status("moe_combine_bwd");
 }

@@ -107,17 +107,41 @@ __global__ __launch_bounds__(64) void dispatch_rank(const int32_t* __restrict__ 
   }
 }
 
-// Xp[row_of[t*k+j], :] = X[t, :], 16 bytes per lane per access
+// Xp[row_of[t*k+j], :] = X[t, :], 16 bytes per lane per access.  K > 0: k known at compile time.
+template <int K>
 __global__ __launch_bounds__(256) void dispatch_rows(const uint4* __restrict__ X,
-                                                     const int32_t* __restrict__ row_of, int k,
+                                                     const int32_t* __restrict__ row_of, int k_rt,
                                                      int vec_per_row, uint4* __restrict__ Xp) {
+  constexpr int KM = K > 0 ? K : 1;
+  const int k = K > 0 ? K : k_rt;
   const int t = blockIdx.x;
   const uint4* src = X + (size_t)t * vec_per_row;
-  for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
-    uint4 v = src[c];
-    for (int j = 0; j < k; j++) {
-      int r = row_of[(size_t)t * k + j];
-      Xp[(size_t)r * vec_per_row + c] = v;
+  if (K > 0) {
+    uint4* dst[KM];
+#pragma unroll
+    for (int j = 0; j < KM; j++) dst[j] = Xp + (size_t)row_of[(size_t)t * k + j] * vec_per_row;
+    // two pieces per thread and trip: both loads are issued before the 2k stores
+    int c = threadIdx.x;
+    for (; c + (int)blockDim.x < vec_per_row; c += 2 * blockDim.x) {
+      const uint4 v0 = src[c], v1 = src[c + blockDim.x];
+#pragma unroll
+      for (int j = 0; j < KM; j++) {
+        dst[j][c] = v0;
+        dst[j][c + blockDim.x] = v1;
+      }
+    }
+    if (c < vec_per_row) {
+      const uint4 v0 = src[c];
+#pragma unroll
+      for (int j = 0; j < KM; j++) dst[j][c] = v0;
+    }
+  } else {
+    for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
+      uint4 v = src[c];
+      for (int j = 0; j < k; j++) {
+        int r = row_of[(size_t)t * k + j];
+        Xp[(size_t)r * vec_per_row + c] = v;
+      }
     }
   }
 }
@@ -170,8 +194,17 @@ extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32
     }
     ProfScope prof("dispatch_rows", st);
     const int vec_per_row = (int)((size_t)shape->d * elem_size(shape->dtype) / 16);
-    hipLaunchKernelGGL(dispatch_rows, dim3(shape->T), dim3(256), 0, st, (const uint4*)X, row_of, shape->k,
-                       vec_per_row, (uint4*)Xp);
+#define MOE_ROWS(K)                                                                                       \
+  hipLaunchKernelGGL(dispatch_rows<K>, dim3(shape->T), dim3(256), 0, st, (const uint4*)X, row_of, shape->k, \
+                     vec_per_row, (uint4*)Xp)
+    switch (shape->k) {
+      case 1: MOE_ROWS(1); break;
+      case 2: MOE_ROWS(2); break;
+      case 4: MOE_ROWS(4); break;
+      case 8: MOE_ROWS(8); break;
+      default: MOE_ROWS(0); break;
+    }
+#undef MOE_ROWS
   }
   return launch_status("moe_dispatch");
 }
