@@ -26,19 +26,25 @@ HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TF = 2500.0   # dense bf16 matrix peak, published
 FP32_VEC_PEAK_TF = 157.3
 
-GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx", "gemm_bwd_dwd", "gemm_bwd_dwgu")
-# kernel symbol behind each profiling label (as rocprofv3 --kernel-trace --stats names them)
+GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx", "gemm_bwd_dwd", "gemm_bwd_dwgu",
+               "gemm_bwd_dwd_light", "gemm_bwd_dwgu_light")
+LIGHT_GROUP_ROWS = 128       # routed experts with at most this many rows take the light weight-gradient kernels
+PROBE_BYTES = 1 << 30        # size of the calibration copy
+PROBE_LAUNCHES = 5
+# kernel behind each profiling label on the bf16 LDS-DMA path, as rocprofv3 names it (one label = one kernel symbol)
 SYMBOL = {
-    "gemm_fwd_gate_up": "row_gemm_kernel<Core<NB=2,A_KC,B rows>, EPI_SWIGLU_FWD>",
-    "gemm_fwd_down": "row_gemm_kernel<Core<NB=1,A_KC,B rows>, EPI_STORE>",
-    "gemm_bwd_dh": "row_gemm_kernel<Core<NB=1,A_KC,B_KC>, EPI_SWIGLU_BWD>",
-    "gemm_bwd_dx": "row_gemm_kernel<Core<NB=1,A_KC,B_KC>, EPI_STORE>",
-    "gemm_bwd_dwd": "w_gemm_kernel<Core<NB=1>>",
-    "gemm_bwd_dwgu": "w_gemm_kernel<Core<NB=2>>",
+    "gemm_fwd_gate_up": "moe::row_gemm_kernel<moe::RowCores<2, 2, false>, 2, 1, false>(moe::RowGemm)",
+    "gemm_fwd_down": "moe::row_gemm_kernel<moe::RowCores<2, 1, false>, 1, 0, false>(moe::RowGemm)",
+    "gemm_bwd_dh": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 2, true>(moe::RowGemm)",
+    "gemm_bwd_dx": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 0, true>(moe::RowGemm)",
+    "gemm_bwd_dwd": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 256, 1, false, false, 2, 2, true>, 1>(moe::WGemm)",
+    "gemm_bwd_dwgu": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 128, 2, false, false, 2, 2, true>, 2>(moe::WGemm)",
+    "gemm_bwd_dwd_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 1, false, false, 2, 2, false>, 1>(moe::WGemm)",
+    "gemm_bwd_dwgu_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 2, false, false, 2, 2, false>, 2>(moe::WGemm)",
 }
 
 
-def algorithmic_work(cfg: wl.MoEConfig):
+def algorithmic_work(cfg: wl.MoEConfig, counts):
     """Per step: FLOPs of each GEMM label over real rows only, bytes of each streaming kernel."""
     b = 4 if cfg.dtype == "f32" else 2
     A, T, d, F, k = cfg.A, cfg.T, cfg.d, cfg.d_ff, cfg.k
@@ -47,6 +53,11 @@ def algorithmic_work(cfg: wl.MoEConfig):
     unit = routed + shared
     flops = {"gemm_fwd_gate_up": 4.0 * unit, "gemm_fwd_down": 2.0 * unit, "gemm_bwd_dh": 2.0 * unit,
              "gemm_bwd_dx": 4.0 * unit, "gemm_bwd_dwd": 2.0 * unit, "gemm_bwd_dwgu": 4.0 * unit}
+    if cfg.dtype == "bf16" and d % 64 == 0 and F % 64 == 0:
+        light = int(counts[counts <= LIGHT_GROUP_ROWS].sum()) * d * F
+        flops["gemm_bwd_dwd_light"], flops["gemm_bwd_dwgu_light"] = 2.0 * light, 4.0 * light
+        flops["gemm_bwd_dwd"] -= 2.0 * light
+        flops["gemm_bwd_dwgu"] -= 4.0 * light
     has_sh = 1 if cfg.n_shared else 0
     byts = {
         "route_kernel": T * cfg.E * 4 + T * k * 8,
@@ -56,6 +67,16 @@ def algorithmic_work(cfg: wl.MoEConfig):
         "combine_bwd_kernel": (1 + 2 * k) * T * d * b + A * 12,
     }
     return flops, byts
+
+
+def measured_traffic(cfg_name, symbol):
+    """HBM bytes per launch of `symbol` from the committed counter summary of this workload, or None."""
+    from paper_2502_02581_amd.rocprof_summary import read_traffic
+
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg_name}.txt")
+    if not os.path.exists(path):
+        return None
+    return read_traffic(path).get(symbol)
 
 
 class LazyExperts:
@@ -154,11 +175,21 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+
+    # one calibration copy of known size (outside the timed region): a profiler's HBM counters are scaled by it
+    probe = torch.empty(2, PROBE_BYTES, dtype=torch.uint8, device=dev)
+    probe.fill_(1)   # touches both halves, so that the copy is not timed on fresh pages
+    for _ in range(PROBE_LAUNCHES):
+        moe.moe_copy_probe(probe[0], probe[1])
+    torch.cuda.synchronize()
     prof = moe.moe_profile_report()
     moe.moe_profile_enable(False)
+    del probe
+    probe_ms = prof.pop("copy_probe_kernel")[1] / PROBE_LAUNCHES
 
     ms_per_step = dt / args.steps * 1e3
-    flops, byts = algorithmic_work(cfg)
+    counts = hp.b["counts"].cpu()
+    flops, byts = algorithmic_work(cfg, counts)
     kernels = {}
     for label, (n, ms) in prof.items():
         per_step_ms = ms / args.steps
@@ -179,9 +210,9 @@ def main():
     roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": dom, "symbol": SYMBOL[dom],
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
-                "flop_per_launch_avg": flops[dom] * args.steps / dom_n, "traffic": None}
+                "flop_per_launch_avg": flops[dom] * args.steps / dom_n,
+                "traffic": measured_traffic(cfg.name, SYMBOL[dom]) if cfg.dtype == "bf16" else None}
 
-    counts = hp.b["counts"].cpu()
     out = {
         "metric": "moe_layer_fwd_bwd_tokens_per_s", "value": round(cfg.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -193,7 +224,9 @@ def main():
                    "load_share_std": round(float((counts.double() / counts.sum()).std(unbiased=False)), 5)},
         "grouped_gemm_tflops": round(gemm_tflops, 2), "grouped_gemm_frac_mfma_peak": round(gemm_tflops / peak, 4),
         "total_tflops": round(cfg.flops()["total"] / (ms_per_step * 1e-3) / 1e12, 2),
-        "roofline": roofline, "kernels": kernels, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
+        "roofline": roofline, "kernels": kernels,
+        "copy_probe": {"bytes_each_way": PROBE_BYTES, "ms": round(probe_ms, 4),
+                       "gbs": round(2 * PROBE_BYTES / (probe_ms * 1e-3) / 1e9, 1)}, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, inp, weights, CPU_SAMPLE_TOKENS[cfg.name])

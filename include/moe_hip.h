@@ -176,6 +176,15 @@ int moe_combine_bwd(const moe_shape_t* shape, const void* dY, const void* Yp, co
 int moe_profile_enable(int on);
 size_t moe_profile_report(char* buf, size_t buf_bytes);
 
+/*
+ * moe_copy_probe -- measurement aid, not part of the hot path: one plain copy kernel
+ * (copy_probe_kernel) moving `bytes` bytes from the device buffer `src` to the device buffer
+ * `dst` (both 16-byte aligned, bytes a positive multiple of 16, no overlap).  It reads and
+ * writes exactly `bytes` bytes of HBM, so a profiler's memory counters for this launch give the
+ * factor that converts counter units into bytes for the other kernels of the same run.
+ */
+int moe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,7 @@ MOE_F32, MOE_BF16 = 0, 1
 MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
 EXPORTS = ["moe_abi_version", "moe_last_error", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
-           "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report"]
+           "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe"]
 
 
 class MoEError(RuntimeError):
@@ -88,6 +88,8 @@ def load_library():
     lib.moe_profile_enable.argtypes = [ctypes.c_int]
     lib.moe_profile_report.restype = sz
     lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
+    lib.moe_copy_probe.restype = ctypes.c_int
+    lib.moe_copy_probe.argtypes = [vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -188,6 +190,15 @@ def moe_combine_bwd(shape: MoEShape, dY, Yp, row_of, topk_w, dYp, dw, stream=Non
                                         _ptr(row_of, torch.int32, "row_of"), _ptr(topk_w, torch.float32, "topk_w"),
                                         _ptr(dYp, dt, "dYp"), _ptr(dw, torch.float32, "dw"), _stream(stream))
     _check(rc, "moe_combine_bwd")
+
+
+def moe_copy_probe(src: torch.Tensor, dst: torch.Tensor):
+    """Copies src to dst (same byte size) with the library's plain copy kernel; calibrates profiler counters."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise MoEError("moe_copy_probe: sizes differ")
+    rc = load_library().moe_copy_probe(_ptr(src), _ptr(dst), ctypes.c_size_t(nbytes), _stream(None))
+    _check(rc, "moe_copy_probe")
 
 
 def moe_profile_enable(on: bool):
