@@ -289,8 +289,31 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, rows, n_valid, epi);
 }
 
+#ifdef MOE_TRACE
+// Development aid (compiled in only with -DMOE_TRACE): one record per tile of the GEMM kernels,
+// {block, kernel id, group, column tile | kind << 8 | rows << 16, start, end}, times from the
+// 100 MHz wall clock; read back through moe_trace_read.
+struct TraceRec {
+  int32_t block, kernel, group, what;
+  unsigned long long t0, t1;
+};
+constexpr int kTraceMax = 1 << 18;
+__device__ TraceRec g_trace[kTraceMax];
+__device__ int g_trace_n;
+__device__ __forceinline__ void trace_put(int kernel, int group, int what, unsigned long long t0) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int i = atomicAdd(&g_trace_n, 1);
+    if (i < kTraceMax) {
+      TraceRec r = {(int32_t)(blockIdx.x + blockIdx.y * gridDim.x), kernel, group, what, t0, (unsigned long long)wall_clock64()};
+      g_trace[i] = r;
+    }
+  }
+}
+#endif
+
 template <class CoreSet, int NB, int EPI, bool B_KC>
-__global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
+__global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel(RowGemm p) {
   extern __shared__ __align__(16) char smem[];
   typedef typename CoreSet::template tile<0> Core0;
   const int ntn = (p.N + Core0::BN - 1) / Core0::BN;
@@ -306,6 +329,9 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
     t.rows = min(Core0::BM, p.n_rows - t.row0_in);
     t.row0_out = t.row0_in;
   }
+#ifdef MOE_TRACE
+  const unsigned long long t_start = (unsigned long long)wall_clock64();
+#endif
   if (CoreSet::kKinds == 1) {
     row_gemm_tile<Core0, NB, EPI, B_KC>(p, t, nt, smem);
   } else {
@@ -316,11 +342,14 @@ __global__ __launch_bounds__(256) void row_gemm_kernel(RowGemm p) {
       default: row_gemm_tile<typename CoreSet::template tile<3>, NB, EPI, B_KC>(p, t, nt, smem); break;
     }
   }
+#ifdef MOE_TRACE
+  trace_put(EPI | (NB << 4) | ((int)B_KC << 8), t.group, nt | (tile_kind(t) << 8) | (tile_rows(t) << 16), t_start);
+#endif
 }
 
 // ------------------------------------------------------------------- weight-gradient kernel
 template <class Core, int NB>
-__global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
+__global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   typedef typename Core::T T;
   extern __shared__ __align__(16) char smem[];
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
@@ -353,7 +382,13 @@ __global__ __launch_bounds__(256) void w_gemm_kernel(WGemm p) {
     Pack<T, W>::store((T*)p.C[0] + off, v[0]);
     if (NB == 2) Pack<T, W>::store((T*)p.C[1] + off, v[NB - 1]);
   };
+#ifdef MOE_TRACE
+  const unsigned long long t_start = (unsigned long long)wall_clock64();
+#endif
   Core::run(smem, (K + BK - 1) / BK, src, p.lda, p.ldb, m_valid, n_valid, epi);
+#ifdef MOE_TRACE
+  trace_put(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16, t_start);
+#endif
 }
 
 // ------------------------------------------------------------------------------ host side
@@ -371,10 +406,11 @@ template <> struct Cores<PATH_BF16> {
 };
 template <> struct Cores<PATH_BF16_DMA> {
   static constexpr int BM = 256, BN = 256;
-  // one block computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each of the two products)
-  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 2>;
+  // one block of 8 wavefronts (two per SIMD, so that one can issue MFMAs while the other waits for a
+  // load slot or a barrier) computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each product)
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 4>;
   // weight gradients of groups with few rows: 128 x 128 outputs per product, one tile slot
-  template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, false>;
+  template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, 0>;
 };
 constexpr int kLightGroupRows = 128;  // groups up to this many rows take the light dW kernel
 
@@ -386,8 +422,13 @@ template <int PATH, int NB, bool B_KC> struct RowCores {
 };
 template <int NB, bool B_KC> struct RowCores<PATH_BF16_DMA, NB, B_KC> {
   static constexpr int kKinds = 4;
+  // tile kinds 0..3 are cut for 256, 128, 64 and 32 rows; the last two share the 64-row core (eight
+  // wavefronts cannot split fewer rows and columns, and those tiles are bound by streaming the
+  // weights, not by MFMA work).  Pipeline depth by height: the 128-row tile fits 3 slots per
+  // operand, the 64-row one 4.
   template <int KIND>
-  using tile = MfmaDmaCore<(256 >> KIND), 256 / NB, NB, true, B_KC, (KIND <= 1 ? 2 : 1), (KIND <= 1 ? 2 : 4)>;
+  using tile = MfmaDmaCore<(KIND == 0 ? 256 : KIND == 1 ? 128 : 64), 256 / NB, NB, true, B_KC, 2, 4,
+                           (KIND == 0 ? 1 : KIND == 1 ? 2 : 3)>;
 };
 
 static int pick_path(const moe_shape_t* s) {
@@ -421,7 +462,7 @@ static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipSt
     attr_done = true;
   }
   ProfScope prof(label, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(n_mt * ntn)), dim3(256), Core::LDS_BYTES, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(n_mt * ntn)), dim3(Core::NT), Core::LDS_BYTES, st, p);
 }
 
 template <class Core, int NB>
@@ -435,7 +476,7 @@ static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_
     attr_done = true;
   }
   ProfScope prof(label, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups), dim3(256), Core::LDS_BYTES, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups), dim3(Core::NT), Core::LDS_BYTES, st, p);
 }
 
 struct FwdArgs {
@@ -660,3 +701,17 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
   }
   return launch_status("moe_expert_bwd");
 }
+
+#ifdef MOE_TRACE
+// copies the trace records to the host buffer (at most max_records), returns their number and clears the trace
+extern "C" int moe_trace_read(void* host, int max_records) {
+  int n = 0;
+  if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(moe::g_trace_n), sizeof(int)) != hipSuccess) return -1;
+  if (n > moe::kTraceMax) n = moe::kTraceMax;
+  if (n > max_records) n = max_records;
+  if (n > 0 && hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_trace), (size_t)n * sizeof(moe::TraceRec)) != hipSuccess) return -1;
+  int zero = 0;
+  (void)hipMemcpyToSymbol(HIP_SYMBOL(moe::g_trace_n), &zero, sizeof(int));
+  return n;
+}
+#endif

@@ -291,27 +291,36 @@ struct MfmaCore {
 //  K-contiguous operand [rows][64]: 16-byte piece c of a row sits at position c ^ ((row/2)%8).
 //  row-contiguous operand [64 k][ROWS]: piece c (8 columns) of k-row k sits at position
 //    c ^ (4*(k%4)), which spreads the four k rows of a transposing read over all banks.
-template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, bool RING = true>
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, int DEPTH = 1>
 struct MfmaDmaCore {
   typedef bf16_t T;
-  static constexpr int BM = BM_, BN = BN_, BK = 64, NT = 256;
+  static constexpr int BM = BM_, BN = BN_, BK = 64;
   static constexpr int WM = WM_, WN = WN_;
+  static constexpr int NW = WM * WN, NT = 64 * NW;  // wavefronts and threads per block
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
-  // LDS: a ring of three A tiles and a ring of two B tile sets.  The A tile of iteration t+2 is
-  // requested while the B tiles of t+1 are still landing, so the memory pipeline never runs dry
-  // at the per-iteration barrier.
-  // RING = false is the variant for groups with very few rows of K (weight gradients of experts
-  // that received a handful of tokens): one tile slot, no software pipeline, small enough in LDS
-  // and registers for several blocks per CU, which is what hides latency when a block's life is
-  // one K iteration and an epilogue.
-  static constexpr int A_SLOTS = RING ? 3 : 1, B_SLOTS = RING ? 2 : 1;
+  // Software pipeline of the K loop, by DEPTH:
+  //  1  (tall tiles, bound by the matrix pipe): a ring of three A tiles and a ring of two B tile
+  //     sets.  The A tile of iteration t+2 is requested while the B tiles of t+1 are still
+  //     landing, so the memory pipeline never runs dry at the per-iteration barrier; MFMAs, LDS
+  //     reads and tile loads are interleaved by hand.
+  //  >= 2  (short tiles of ragged groups, bound by streaming the other operand from HBM): DEPTH + 1
+  //     slots per operand and the loads of iteration t + DEPTH issued in iteration t, so that DEPTH
+  //     whole K steps are in flight per CU; the latency of an HBM stream, not the matrix pipe, sets
+  //     the pace there.
+  //  0  (weight gradients of groups with a handful of rows: K is one or two steps): one slot, no
+  //     pipeline, small enough in LDS and registers for several blocks per CU, which is what hides
+  //     latency when a block's life is one K iteration and an epilogue.
+  static constexpr bool RING = DEPTH == 1;
+  static constexpr int A_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 3 : DEPTH + 1;
+  static constexpr int B_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 2 : DEPTH + 1;
   static constexpr int B_SET_ELEMS = NB * B_ELEMS;
   static constexpr int TILE_BYTES = (A_SLOTS * A_ELEMS + B_SLOTS * B_SET_ELEMS) * 2;
-  static constexpr int STAGING_BYTES = 4 * NB * 32 * ((BN_ / WN_) + 4) * 4;  // epilogue, see run()
+  static constexpr int STAGING_BYTES = NW * NB * 32 * ((BN_ / WN_) + 4) * 4;  // epilogue, see run()
   static constexpr int LDS_BYTES = TILE_BYTES > STAGING_BYTES ? TILE_BYTES : STAGING_BYTES;
-  static constexpr int A_NI = BM / 32, B_NI = BN / 32;  // wave-wide loads per wave and tile
-  static_assert(WM * WN == 4, "four wavefronts per block");
+  static constexpr int A_NI = BM / (8 * NW), B_NI = BN / (8 * NW);  // wave-wide loads per wave and tile
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wave issues the same number of 1 KB loads per tile");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
   static_assert((A_KC || BM % 128 == 0) && (B_KC || BN % 128 == 0),
                 "swizzle of row-contiguous tiles needs >= 16 pieces per k row");
@@ -337,9 +346,9 @@ struct MfmaDmaCore {
     }
   }
   // rows of the memory operand (K-contiguous: tile rows; row-contiguous: k rows) between two
-  // consecutive loads of a wave: four waves x 1 KB = 4 KB of LDS tile per round
+  // consecutive loads of a wave: NW waves x 1 KB of LDS tile per round
   template <int ROWS, bool KC>
-  __device__ static constexpr int load_stride() { return KC ? 32 : 2048 / ROWS; }
+  __device__ static constexpr int load_stride() { return KC ? 8 * NW : 512 * NW / ROWS; }
 
   // One wave-wide 16-byte-per-lane load straight into LDS: the n-th 1 KB piece of this wave's share
   // of a tile.  Written as inline assembly so that the compiler does not serialise it against the
@@ -357,7 +366,7 @@ struct MfmaDmaCore {
     rsrc[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
     rsrc[2] = __builtin_amdgcn_readfirstlane((int)(bytes > skip ? bytes - skip : 0u));
     rsrc[3] = 0x00020000;
-    const uint32_t dst = lds_tile_addr + (uint32_t)(j * 4 + wave) * 1024u;
+    const uint32_t dst = lds_tile_addr + (uint32_t)(j * NW + wave) * 1024u;
     // The compiler's hazard recogniser does not look inside inline assembly.  Two hazards of this
     // hardware generation apply here: an SGPR written by a VALU instruction (v_readfirstlane, which
     // the compiler uses to make descriptor words uniform) must not be read by a vector memory
@@ -492,7 +501,41 @@ struct MfmaDmaCore {
     lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
 
     constexpr int kLoadsB = NB * B_NI;  // loads per wave for the B tiles of one iteration
-    if constexpr (!RING) {
+    if constexpr (DEPTH >= 2) {
+      // streaming pipeline: tiles t .. t+DEPTH-1 in flight while tile t is multiplied
+      constexpr int L = A_NI + kLoadsB;  // loads per wave and iteration
+      static_assert((DEPTH - 1) * L <= 63, "the wait count of the oldest tile must be encodable");
+      auto issue_tile = [&](int it) __attribute__((always_inline)) {
+        const IterSrc<bf16_t, NB> s0 = source(it);
+        const int slot = it % (DEPTH + 1);
+#pragma unroll
+        for (int j = 0; j < A_NI; j++) load_a(s0, slot, j);
+#pragma unroll
+        for (int n = 0; n < kLoadsB; n++) load_b(s0, slot, n);
+      };
+      if (n_iters > 0) {
+        for (int it = 0; it < DEPTH; it++) issue_tile(it);
+      }
+      for (int it = 0; it < n_iters; it++) {
+        // tile `it` has landed once at most the DEPTH - 1 younger tiles are outstanding (loads
+        // complete in order); the barrier also says that every wave is done with tile it - 1,
+        // whose slot the loads of tile it + DEPTH overwrite
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * L) : "memory");
+        __syncthreads();
+        issue_tile(it + DEPTH);
+        const int slot = it % (DEPTH + 1);
+        const bf16_t* As = lds + slot * A_ELEMS;
+        const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + slot * B_SET_ELEMS;
+#pragma unroll
+        for (int ks = 0; ks < 4; ks++) {
+          Frags f;
+#pragma unroll
+          for (int r = 0; r < kFragLoads; r++) load_frag_n(As, Bs, ao, bo, ks, r, f);
+#pragma unroll
+          for (int m = 0; m < kMfma; m++) mfma_n(acc, f, m);
+        }
+      }
+    } else if constexpr (!RING) {
       // single slot: load a tile, wait, multiply; k-steps beyond the rows of K are skipped
       for (int it = 0; it < n_iters; it++) {
         const IterSrc<bf16_t, NB> s0 = source(it);
@@ -619,8 +662,8 @@ struct MfmaDmaCore {
     constexpr int RS = CW + 4;           // row stride of the staging region, in floats
     constexpr int LPR = CW / 8;          // lanes per row when reading back
     constexpr int RPP = 64 / LPR;        // rows per read pass
-    static_assert(4 * NB * 32 * RS * 4 <= LDS_BYTES, "staging regions of the four waves fit into LDS");
-    static_assert(4 * NB * 32 * RS * 4 == STAGING_BYTES, "STAGING_BYTES matches the staging layout");
+    static_assert(NW * NB * 32 * RS * 4 <= LDS_BYTES, "staging regions of the waves fit into LDS");
+    static_assert(NW * NB * 32 * RS * 4 == STAGING_BYTES, "STAGING_BYTES matches the staging layout");
     float* stage = reinterpret_cast<float*>(smem) + wave * (NB * 32 * RS);
 #pragma unroll
     for (int i = 0; i < TM; i++) {
