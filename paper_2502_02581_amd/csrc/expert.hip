@@ -43,11 +43,8 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   st_[e] = st;
   sc[e] = (e < n_groups && c > 0) ? 1 : 0;
   __syncthreads();
-  // Launch order of the groups.  Sorted by descending row count, the heavy groups (MFMA-bound) would
-  // all run before the light ones (bound by streaming their weights from HBM), and the two
-  // resources would be used one after the other.  So the light groups (at most kLightRows rows) are
-  // spread evenly, by cumulative rows, between the heavy ones: a stable merge of two sorted lists.
-  constexpr int kLightRows = 128;
+  // Launch order of the groups: descending row count (ties: ascending id), so that the short tiles
+  // of the light groups fill the end of a launch.
   int rank = 0;
   if (e < n_groups) {
     for (int o = 0; o < n_groups; o++) {
@@ -57,56 +54,6 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
     ord[rank] = e;
   }
   __syncthreads();
-  {
-    // thread e now looks at the group of sorted rank e
-    const int ge = e < n_groups ? ord[e] : 0;
-    const int ce = e < n_groups ? cnt[ge] : 0;
-    const bool heavy = e < n_groups && ce > kLightRows;
-    st_[e] = heavy ? ce : 0;  // scratch: rows of heavy groups in sorted order
-    __syncthreads();
-    int n_heavy = 0;
-    long long total = 0, before = 0;
-    for (int o = 0; o < n_groups; o++) {
-      if (st_[o] > 0) {
-        n_heavy++;
-        total += st_[o];
-        if (o < e) before += st_[o];
-      }
-    }
-    const int n_light = n_groups - n_heavy;
-    int pos = e;
-    if (e < n_groups && n_heavy > 0 && n_light > 0) {
-      if (heavy) {
-        // lights whose target (l + 0.5) / n_light * total lies before this group's first row
-        // target_l < before  <=>  (2l + 1) * total < 2 * before * n_light
-        long long lim = 2 * before * n_light;
-        int nl = (int)min((long long)n_light, lim <= total ? 0ll : (lim - total + 2 * total - 1) / (2 * total));
-        pos = e + nl;  // e heavy groups precede it in sorted order (heavy ones sort first)
-      } else {
-        const int l = e - n_heavy;
-        // heavy groups whose first row is at or before the target: before_h * 2 * n_light <= (2l+1) * total
-        int nh = 0;
-        long long acc = 0;
-        for (int o = 0; o < n_heavy; o++) {
-          nh += (2 * acc * n_light <= (2ll * l + 1) * total);
-          acc += st_[o];
-        }
-        pos = l + nh;
-      }
-    }
-    __syncthreads();
-    if (e < n_groups) {
-      sc[pos] = ge;  // scratch: merged order
-    }
-    __syncthreads();
-    if (e < n_groups) ord[e] = sc[e];
-    __syncthreads();
-  }
-  if (e < n_groups) {
-    pl.order[e] = ord[e];
-    pl.counts[e] = c;
-    pl.starts[e] = st;
-  }
   st_[e] = st;
   sc[e] = (e < n_groups && c > 0) ? 1 : 0;
   __syncthreads();
@@ -114,12 +61,12 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
   const int total_active = sc[1023];
   if (e < n_groups) {
     const int slot = c > 0 ? sc[e] - 1 : -1;
-    pl.slot_of[e] = slot;
     if (active_ids) {
       if (slot >= 0) active_ids[slot] = e;
       if (e >= total_active) active_ids[e] = -1;
     }
   }
+  if (e < n_groups) pl.ginfo[rank] = make_int4(e, c, st, c > 0 ? sc[e] - 1 : -1);
   if (e == 0 && n_active) *n_active = total_active;
   __syncthreads();
   // Row tiles, groups in descending size.  BM > 0: tiles of BM rows.  BM == 0: mixed heights -- full
@@ -353,11 +300,11 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   typedef typename Core::T T;
   extern __shared__ __align__(16) char smem[];
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
-  const int g = p.order ? p.order[blockIdx.y] : blockIdx.y;
-  const int K = p.counts ? p.counts[g] : p.n_rows;
+  const int4 gi = p.ginfo[blockIdx.y];  // {group, rows, first row, compact slot}
+  const int g = gi.x, K = gi.y, start = gi.z, slot = gi.w;
   if (K <= 0 || K < p.k_min || K > p.k_max) return;
-  const int start = p.starts ? p.starts[g] : 0;
-  const int slot = p.slot_of ? p.slot_of[g] : g;
+  // single-product kernels serve the two products of a dual GEMM through blockIdx.z
+  const int z = NB == 1 ? blockIdx.z : 0;
   const int ntn = (p.N + BN - 1) / BN;
   const int m0 = (blockIdx.x / ntn) * BM, n0 = (blockIdx.x % ntn) * BN;
   const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
@@ -367,7 +314,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
     IterSrc<T, NB> s;
     const int k0 = it * BK;
     s.a = (const T*)p.A + (int64_t)(a_row0 + k0) * p.lda + m0;
-    s.b[0] = (const T*)p.B[0] + (int64_t)(b_row0 + k0) * p.ldb + n0;
+    s.b[0] = (const T*)p.B[z] + (int64_t)(b_row0 + k0) * p.ldb + n0;
     if (NB == 2) s.b[NB - 1] = (const T*)p.B[1] + (int64_t)(b_row0 + k0) * p.ldb + n0;
     s.k_left = K - k0;
     const int64_t es = sizeof(T);
@@ -379,7 +326,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
     constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= m_valid || n >= n_valid) return;
     const int64_t off = (int64_t)slot * p.c_slot + (int64_t)(m0 + m) * p.N + n0 + n;
-    Pack<T, W>::store((T*)p.C[0] + off, v[0]);
+    Pack<T, W>::store((T*)p.C[z] + off, v[0]);
     if (NB == 2) Pack<T, W>::store((T*)p.C[1] + off, v[NB - 1]);
   };
 #ifdef MOE_TRACE
@@ -466,7 +413,7 @@ static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipSt
 }
 
 template <class Core, int NB>
-static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_t st) {
+static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_t st, int n_products = 1) {
   const int tiles = ceil_div(p.M, Core::BM) * ceil_div(p.N, Core::BN);
   if (tiles == 0 || n_groups == 0) return;
   auto kern = w_gemm_kernel<Core, NB>;
@@ -476,7 +423,7 @@ static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_
     attr_done = true;
   }
   ProfScope prof(label, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups), dim3(Core::NT), Core::LDS_BYTES, st, p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups, (unsigned)n_products), dim3(Core::NT), Core::LDS_BYTES, st, p);
 }
 
 struct FwdArgs {
@@ -570,13 +517,13 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   launch_row<RowCores<PATH, 1, true>, 1, EPI_STORE, true>("gemm_bwd_dx", q, max_tiles, st);
   // B3: weight gradients, compacted to active groups, largest group first
   WGemm w = {};
-  w.order = pl.order; w.slot_of = pl.slot_of; w.counts = pl.counts; w.starts = pl.starts; w.n_rows = a.n_rows;
+  w.ginfo = pl.ginfo; w.n_rows = a.n_rows;
   w.M = a.F; w.N = a.d;
   w.A = a.H; w.lda = a.F; w.a_per_group = shared;
   w.B[0] = a.dYin; w.ldb = a.d; w.b_per_group = 0;
   w.C[0] = a.dWd; w.c_slot = (int64_t)a.F * a.d;
   WGemm v = {};
-  v.order = pl.order; v.slot_of = pl.slot_of; v.counts = pl.counts; v.starts = pl.starts; v.n_rows = a.n_rows;
+  v.ginfo = pl.ginfo; v.n_rows = a.n_rows;
   v.M = a.d; v.N = a.F;
   v.A = a.Xin; v.lda = a.d; v.a_per_group = 0;
   v.B[0] = dG; v.B[1] = dU; v.ldb = a.F; v.b_per_group = shared;
@@ -594,7 +541,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
       launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
       launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dwd_light", wl_, a.n_groups, st);
-      launch_w<typename C::template core_light<2>, 2>("gemm_bwd_dwgu_light", vl_, a.n_groups, st);
+      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dwgu_light", vl_, a.n_groups, st, 2);
       return;
     }
   }

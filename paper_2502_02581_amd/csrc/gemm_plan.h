@@ -9,12 +9,12 @@ namespace moe {
 struct RowTile {
   int32_t group;     // expert that owns the rows
   int32_t row0_in;   // first row in the [n_rows, .] input/output of the call
-  int32_t rows;      // valid rows (<= tile height) in the low 16 bits, tile kind in the high 16 bits
+  int32_t rows;      // valid rows (<= tile height) in bits 0..15, tile kind in bits 16..17
   int32_t row0_out;  // first row in the per-group saved activations (differs in shared mode)
 };
 
 __host__ __device__ inline int tile_rows(const RowTile& t) { return t.rows & 0xffff; }
-__host__ __device__ inline int tile_kind(const RowTile& t) { return t.rows >> 16; }
+__host__ __device__ inline int tile_kind(const RowTile& t) { return (t.rows >> 16) & 3; }
 // heights of the tile kinds of the mixed-height plan (kind 0 is the full tile)
 __host__ __device__ inline int kind_height(int kind) { return 256 >> kind; }
 
@@ -22,14 +22,11 @@ __host__ __device__ inline int kind_height(int kind) { return 256 >> kind; }
 struct Plan {
   RowTile* tiles;      // [max_tiles]
   int32_t* n_tiles;    // [1]
-  int32_t* order;      // [n_groups] groups by descending row count (ties: ascending id)
-  int32_t* slot_of;    // [n_groups] compact slot of an active group, -1 otherwise
-  int32_t* counts;     // [n_groups]
-  int32_t* starts;     // [n_groups] first row of the group
+  int4* ginfo;         // [n_groups] {group, rows, first row, compact slot} by descending row count
 };
 
 inline size_t plan_bytes(int n_groups, int max_tiles) {
-  return align_up((size_t)max_tiles * sizeof(RowTile), 256) + 256 + 4 * align_up((size_t)n_groups * 4, 256);
+  return align_up((size_t)max_tiles * sizeof(RowTile), 256) + 256 + align_up((size_t)n_groups * sizeof(int4), 256);
 }
 
 inline Plan carve_plan(void* ws, int n_groups, int max_tiles) {
@@ -39,14 +36,7 @@ inline Plan carve_plan(void* ws, int n_groups, int max_tiles) {
   p += align_up((size_t)max_tiles * sizeof(RowTile), 256);
   pl.n_tiles = (int32_t*)p;
   p += 256;
-  size_t g = align_up((size_t)n_groups * 4, 256);
-  pl.order = (int32_t*)p;
-  p += g;
-  pl.slot_of = (int32_t*)p;
-  p += g;
-  pl.counts = (int32_t*)p;
-  p += g;
-  pl.starts = (int32_t*)p;
+  pl.ginfo = (int4*)p;
   return pl;
 }
 
@@ -72,16 +62,13 @@ struct RowGemm {
 
 // per group: C[M, N] = A_g^T B_g over the rows of the group (K = rows of the group)
 struct WGemm {
-  const int32_t* order;     // NULL: identity
-  const int32_t* slot_of;   // NULL: slot = group
-  const int32_t* counts;    // NULL: every group has n_rows rows
-  const int32_t* starts;
+  const int4* ginfo;        // per launch index (descending rows): {group, rows, first row, compact slot}
   int32_t n_rows;
   int32_t M, N;
   const void* A;            // element (row, m) at A + row*lda + m
   int64_t lda;
   int32_t a_per_group;      // shared mode: A rows of group g start at g*n_rows
-  const void* B[2];         // element (row, n) at B + row*ldb + n; B[1] for the dual GEMM
+  const void* B[2];         // element (row, n) at B + row*ldb + n; B[1]: second product (dual GEMM, or blockIdx.z = 1)
   int64_t ldb;
   int32_t b_per_group;
   void* C[2];
