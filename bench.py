@@ -2,7 +2,7 @@
 """Benchmark of the MoE-layer hot path on one MI355X.
 
 One "step" is one forward+backward pass of the whole path (route, dispatch, routed and shared
-expert grouped GEMMs, combine; combine-bwd, dH/dX/dW grouped GEMMs with compacted dW, un-permute)
+expert grouped GEMMs, combine; combine-bwd, dH/dX/dW grouped GEMMs with compacted dW, un-permute, gate backward)
 over one batch of seeded synthetic input that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config dsv3|qwen|phi|stress|tiny]
@@ -27,7 +27,7 @@ MFMA_BF16_PEAK_TF = 2500.0   # dense bf16 matrix peak, published
 FP32_VEC_PEAK_TF = 157.3
 
 GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx", "gemm_bwd_dwd", "gemm_bwd_dwgu",
-               "gemm_bwd_dwd_light", "gemm_bwd_dwgu_light")
+               "gemm_bwd_dw_light")
 LIGHT_GROUP_ROWS = 128       # routed experts with at most this many rows take the light weight-gradient kernels
 PROBE_BYTES = 1 << 30        # size of the calibration copy
 PROBE_LAUNCHES = 5
@@ -37,10 +37,9 @@ SYMBOL = {
     "gemm_fwd_down": "moe::row_gemm_kernel<moe::RowCores<2, 1, false>, 1, 0, false>(moe::RowGemm)",
     "gemm_bwd_dh": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 2, true>(moe::RowGemm)",
     "gemm_bwd_dx": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 0, true>(moe::RowGemm)",
-    "gemm_bwd_dwd": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 256, 1, false, false, 2, 2, true>, 1>(moe::WGemm)",
-    "gemm_bwd_dwgu": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 128, 2, false, false, 2, 2, true>, 2>(moe::WGemm)",
-    "gemm_bwd_dwd_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 1, false, false, 2, 2, false>, 1>(moe::WGemm)",
-    "gemm_bwd_dwgu_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 2, false, false, 2, 2, false>, 2>(moe::WGemm)",
+    "gemm_bwd_dwd": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 256, 1, false, false, 2, 4, 1>, 1>(moe::WGemm)",
+    "gemm_bwd_dwgu": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 128, 2, false, false, 2, 4, 1>, 2>(moe::WGemm)",
+    "gemm_bwd_dw_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 1, false, false, 2, 2, 0>, 1>(moe::WGemm)",
 }
 
 
@@ -55,12 +54,13 @@ def algorithmic_work(cfg: wl.MoEConfig, counts):
              "gemm_bwd_dx": 4.0 * unit, "gemm_bwd_dwd": 2.0 * unit, "gemm_bwd_dwgu": 4.0 * unit}
     if cfg.dtype == "bf16" and d % 64 == 0 and F % 64 == 0:
         light = int(counts[counts <= LIGHT_GROUP_ROWS].sum()) * d * F
-        flops["gemm_bwd_dwd_light"], flops["gemm_bwd_dwgu_light"] = 2.0 * light, 4.0 * light
+        flops["gemm_bwd_dw_light"] = 6.0 * light  # two launches: dWd, then dWg and dWu
         flops["gemm_bwd_dwd"] -= 2.0 * light
         flops["gemm_bwd_dwgu"] -= 4.0 * light
     has_sh = 1 if cfg.n_shared else 0
     byts = {
         "route_kernel": T * cfg.E * 4 + T * k * 8,
+        "route_bwd_kernel": 2 * T * cfg.E * 4 + T * k * 8,
         "dispatch_rows": (1 + k) * T * d * b + A * 4,
         # two launches per step: Y (weights, + shared output) and dX (unit weights, + shared dX)
         "combine_kernel": 2 * ((k + 1 + has_sh) * T * d * b + A * 4) + A * 4,

@@ -88,6 +88,20 @@ int moe_route(const moe_shape_t* shape, const float* logits, int32_t* topk_idx, 
               void* stream);
 
 /*
+ * moe_route_bwd -- backward of the gate of Eq. 3 with the selection held fixed (top-k is
+ * piecewise constant): the gradient of the loss with respect to the router logits from the
+ * gradient dw of the combine weights (moe_combine_bwd).
+ *   w_j = s_j / sum_i s_i (renorm) or s_j, s = softmax(logits) or sigmoid(logits):
+ *   ds_j = (dw_j - sum_i dw_i w_i) / sum_i s_i (renorm) or dw_j;  ds_e = 0 for unselected e;
+ *   softmax: dlogits_e = s_e (ds_e - sum_j s_j ds_j);   sigmoid: dlogits_e = ds_e s_e (1 - s_e).
+ *   logits [T, E] f32;  topk_idx [T, k] i32 from moe_route;  dw [T, k] f32;
+ *   dlogits [T, E] f32 out (every element is written)
+ * topk_idx entries outside 0..E-1 are a caller error (result unspecified).
+ */
+int moe_route_bwd(const moe_shape_t* shape, const float* logits, const int32_t* topk_idx, const float* dw,
+                  float* dlogits, void* stream);
+
+/*
  * moe_dispatch -- group the T*k token-expert assignments by expert and copy the token rows
  * into expert-contiguous order (the local-dispatch case of Algorithm 3: counts[e] is its
  * token assignment T[e, d] for this device; no token is dropped).

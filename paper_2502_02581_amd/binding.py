@@ -14,7 +14,7 @@ _lib = None
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
-EXPORTS = ["moe_abi_version", "moe_last_error", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
+EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe"]
 
@@ -74,6 +74,8 @@ def load_library():
         f.argtypes = [shp, i32, i32, i32]
     lib.moe_route.restype = ctypes.c_int
     lib.moe_route.argtypes = [shp, vp, vp, vp, vp]
+    lib.moe_route_bwd.restype = ctypes.c_int
+    lib.moe_route_bwd.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.moe_dispatch.restype = ctypes.c_int
     lib.moe_dispatch.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_expert_fwd.restype = ctypes.c_int
@@ -142,6 +144,13 @@ def moe_route(shape: MoEShape, logits, topk_idx, topk_w, stream=None):
                                   _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"),
                                   _stream(stream))
     _check(rc, "moe_route")
+
+
+def moe_route_bwd(shape: MoEShape, logits, topk_idx, dw, dlogits, stream=None):
+    rc = load_library().moe_route_bwd(ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"),
+                                      _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(dw, torch.float32, "dw"),
+                                      _ptr(dlogits, torch.float32, "dlogits"), _stream(stream))
+    _check(rc, "moe_route_bwd")
 
 
 def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, ws, stream=None):
@@ -222,6 +231,7 @@ class MoEHotPath:
 
     forward():  moe_route -> moe_dispatch -> moe_expert_fwd (routed, then shared) -> moe_combine
     backward(): moe_combine_bwd -> moe_expert_bwd (routed, then shared) -> moe_combine (unit weights)
+                -> moe_route_bwd (gradient of the router logits)
     No arithmetic happens here; tensors are only allocated and handed to the library.
     """
 
@@ -238,6 +248,7 @@ class MoEHotPath:
             "Xp": torch.empty(A, s.d, **f), "G": torch.empty(A, s.d_ff, **f), "U": torch.empty(A, s.d_ff, **f),
             "H": torch.empty(A, s.d_ff, **f), "Yp": torch.empty(A, s.d, **f), "Y": torch.empty(s.T, s.d, **f),
             "dYp": torch.empty(A, s.d, **f), "dw": torch.empty(s.T, s.k, dtype=torch.float32, device=dev),
+            "dlogits": torch.empty(s.T, s.E, dtype=torch.float32, device=dev),
             "dXp": torch.empty(A, s.d, **f), "dX": torch.empty(s.T, s.d, **f),
             "active_ids": torch.empty(s.E, **i32), "n_active": torch.empty(1, **i32),
             "dWg_c": torch.empty(s.E, s.d, s.d_ff, **f), "dWu_c": torch.empty(s.E, s.d, s.d_ff, **f),
@@ -262,6 +273,7 @@ class MoEHotPath:
     def forward(self, logits, X, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, stream=None):
         s, b = self.shape, self.b
         A = s.T * s.k
+        self._logits = logits  # the gate's backward reads them again
         moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
         moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
         moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
@@ -281,4 +293,5 @@ class MoEHotPath:
             moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
                            b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws, stream)
         moe_combine(s, b["dXp"], b["row_of"], None, b["dXsh"] if self.S else None, b["dX"], stream)
+        moe_route_bwd(s, self._logits, b["topk_idx"], b["dw"], b["dlogits"], stream)
         return b["dX"]

@@ -8,7 +8,7 @@ namespace moe {
 // K > 0: k known at compile time (all loops unrolled, the k gathered loads of a piece are in flight
 // together); K == 0: any k.
 template <typename T, int K>
-__global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ Yp,
+__global__ __launch_bounds__(512) void combine_kernel(const T* __restrict__ Yp,
                                                       const int32_t* __restrict__ row_of,
                                                       const float* __restrict__ topk_w,
                                                       const T* Yadd, T* Y, int d, int k_rt) {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const T* __restrict__ Yp,
 // dYp rows and the k dot products of one token.  The partial dots stay in registers over the whole
 // row; one wave reduction per slot and one exchange through LDS per token.
 template <typename T, int K>
-__global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ dY, const T* __restrict__ Yp,
+__global__ __launch_bounds__(512) void combine_bwd_kernel(const T* __restrict__ dY, const T* __restrict__ Yp,
                                                           const int32_t* __restrict__ row_of,
                                                           const float* __restrict__ topk_w,
                                                           T* __restrict__ dYp, float* __restrict__ dw, int d,
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
   constexpr int N = Vec16<T>::N;
   constexpr int KM = K > 0 ? K : 1;
   const int k = K > 0 ? K : k_rt;
-  __shared__ float part[4][KM > 1 ? KM : 1];
+  __shared__ float part[8][KM > 1 ? KM : 1];
   const int t = blockIdx.x;
   const int vec_per_row = d / N;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -109,9 +109,11 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
       if (lane == 0) part[wave][j] = s;
     }
     __syncthreads();
-    if (threadIdx.x < KM)
-      dw[(size_t)t * k + threadIdx.x] =
-          (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+    if (threadIdx.x < KM) {
+      float s = 0.f;  // fixed order over the waves of the block
+      for (int wv = 0; wv < (int)(blockDim.x >> 6); wv++) s += part[wv][threadIdx.x];
+      dw[(size_t)t * k + threadIdx.x] = s;
+    }
   } else {
     for (int j = 0; j < k; j++) {
       const size_t r = (size_t)row_of[(size_t)t * k + j] * d;
@@ -131,16 +133,30 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const T* __restrict__ 
       dot = wave_sum(dot);
       if (lane == 0) part[wave][0] = dot;
       __syncthreads();
-      if (threadIdx.x == 0) dw[(size_t)t * k + j] = (part[0][0] + part[1][0]) + (part[2][0] + part[3][0]);
+      if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int wv = 0; wv < (int)(blockDim.x >> 6); wv++) s += part[wv][0];
+        dw[(size_t)t * k + j] = s;
+      }
       __syncthreads();
     }
   }
 }
 
+// Threads per token block: the 16-byte pieces of a row are spread over as few equal trips as fit 512
+// threads, so that no lane idles in the last trip (d = 7168 in bf16: 896 pieces = 2 trips of 448).
+static unsigned row_block_threads(int d, int elems_per_piece) {
+  const int pieces = d / elems_per_piece;
+  const int trips = (pieces + 511) / 512;
+  const int per_trip = (pieces + trips - 1) / trips;
+  const int threads = (per_trip + 63) / 64 * 64;
+  return (unsigned)(threads < 64 ? 64 : threads);
+}
+
 template <typename T>
 static void launch_combine(const moe_shape_t* s, const void* Yp, const int32_t* row_of, const float* topk_w,
                            const void* Yadd, void* Y, hipStream_t st) {
-  dim3 grid(s->T), block(256);
+  dim3 grid(s->T), block(row_block_threads(s->d, Vec16<T>::N));
 #define MOE_COMBINE(K)                                                                                       \
   hipLaunchKernelGGL((combine_kernel<T, K>), grid, block, 0, st, (const T*)Yp, row_of, topk_w, (const T*)Yadd, \
                      (T*)Y, s->d, s->k)
@@ -157,7 +173,7 @@ static void launch_combine(const moe_shape_t* s, const void* Yp, const int32_t* 
 template <typename T>
 static void launch_combine_bwd(const moe_shape_t* s, const void* dY, const void* Yp, const int32_t* row_of,
                                const float* topk_w, void* dYp, float* dw, hipStream_t st) {
-  dim3 grid(s->T), block(256);
+  dim3 grid(s->T), block(row_block_threads(s->d, Vec16<T>::N));
 #define MOE_COMBINE_BWD(K)                                                                                    \
   hipLaunchKernelGGL((combine_bwd_kernel<T, K>), grid, block, 0, st, (const T*)dY, (const T*)Yp, row_of, topk_w, \
                      (T*)dYp, dw, s->d, s->k)

@@ -540,8 +540,8 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       wl_.k_max = vl_.k_max = kLightGroupRows;
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
       launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
-      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dwd_light", wl_, a.n_groups, st);
-      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dwgu_light", vl_, a.n_groups, st, 2);
+      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dw_light", wl_, a.n_groups, st);
+      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dw_light", vl_, a.n_groups, st, 2);
       return;
     }
   }

@@ -3,8 +3,8 @@
 The oracle cannot run a whole 2-20 TFLOP layer in test time, so at full size:
   * every integer output (top-k indices, counts, offsets, permutations, active ids) and the combine
     weights are compared in full, bit-exactly / to 1e-5;
-  * Y, dX and dw are compared on sampled tokens, each computed by the oracle straight from Eq. 3
-    (oracle.token_fwd_bwd: the token's k experts and the shared experts);
+  * Y, dX, dw and dlogits are compared on sampled tokens, each computed by the oracle straight from
+    Eq. 3 (oracle.token_fwd_bwd: the token's k experts and the shared experts; oracle.route_bwd);
   * the compacted weight gradients are compared in full for sampled experts (a mid-size one, the
     median one and the smallest active one), each recomputed by the oracle from its own rows;
   * the shared experts' weight gradients are compared in full for one shared expert.
@@ -92,9 +92,11 @@ def test_full_size_sampled(name):
         ref_dx.append(dx)
         ref_dw.append(dw)
     tt = torch.tensor(toks)
+    ref_dlg = orc.route_bwd(lg[toks], idx[toks], np.stack(ref_dw), cfg.gate, cfg.renorm)
     errs = {"Y": scale_rel_err(b["Y"].cpu()[tt], np.stack(ref_y)),
             "dX": scale_rel_err(b["dX"].cpu()[tt], np.stack(ref_dx)),
-            "dw": scale_rel_err(b["dw"].cpu()[tt], np.stack(ref_dw))}
+            "dw": scale_rel_err(b["dw"].cpu()[tt], np.stack(ref_dw)),
+            "dlogits": scale_rel_err(b["dlogits"].cpu()[tt], ref_dlg)}
 
     # ---- sampled experts: compact dW in full, recomputed from the expert's own rows
     active = [int(e) for e in ids[:int(n_act)]]

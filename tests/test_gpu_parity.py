@@ -43,7 +43,7 @@ def run_gpu(cfg, p):
 def run_oracle(cfg, p):
     o = oracle_inputs(p)
     return orc.layer_fwd_bwd(o["logits"], o["X"], o["dY"], o["Wg"], o["Wu"], o["Wd"], cfg.k, cfg.gate, cfg.renorm,
-                             o.get("Wsg"), o.get("Wsu"), o.get("Wsd"))
+                             o.get("Wsg"), o.get("Wsu"), o.get("Wsd"), want_dlogits=True)
 
 
 def compare_layer(cfg, got, ref):
@@ -56,7 +56,7 @@ def compare_layer(cfg, got, ref):
     errs = {}
     errs["topk_w"] = scale_rel_err(got["topk_w"], ref["topk_w"])
     assert errs["topk_w"] <= 1e-5
-    fp = ["Xp", "G", "U", "H", "Yp", "Y", "dYp", "dw", "dXp", "dX"]
+    fp = ["Xp", "G", "U", "H", "Yp", "Y", "dYp", "dw", "dXp", "dX", "dlogits"]
     if cfg.n_shared:
         fp += ["Ysh", "dXsh", "dWsg", "dWsu", "dWsd"]
     for key in fp:
@@ -184,6 +184,25 @@ def test_route_dispatch_shapes(E, k):
     for got, exp in zip(("counts", "offsets", "row_of", "src_of"), ref):
         assert np.array_equal(out[got].cpu().numpy(), exp), got
     assert torch.equal(Xp.cpu(), X.cpu()[torch.arange(T * k) // k][torch.from_numpy(ref[3]).long()])
+
+
+@pytest.mark.parametrize("E,k", [(1, 1), (8, 8), (64, 3), (65, 2), (256, 8), (300, 6), (1024, 64)])
+@pytest.mark.parametrize("gate", ["softmax", "sigmoid"])
+@pytest.mark.parametrize("renorm", [True, False])
+def test_route_bwd(E, k, gate, renorm):
+    """Gradient of the router logits from given dw, against the oracle's route_bwd (fp32 arithmetic: 1e-4)."""
+    import paper_2502_02581_amd as moe
+
+    T = 203
+    cfg = small_cfg(T=T, d=8, E=E, k=k, d_ff=8, zipf_s=1.2, seed=5)
+    lg = wl.make_logits(cfg)
+    dw = torch.randn(T, k, generator=torch.Generator().manual_seed(11))
+    shape = moe.MoEShape(T, 8, E, k, 8, "f32", gate, renorm)
+    ridx, _ = orc.route(lg.numpy(), k, gate, renorm)
+    ref = orc.route_bwd(lg.numpy(), ridx, dw.numpy(), gate, renorm)
+    out = torch.full((T, E), float("nan"), device="cuda")
+    moe.moe_route_bwd(shape, lg.cuda(), torch.from_numpy(ridx).cuda(), dw.cuda(), out)
+    assert scale_rel_err(out.cpu(), ref) <= 1e-4
 
 
 def test_determinism():
