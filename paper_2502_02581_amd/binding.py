@@ -233,10 +233,17 @@ class MoEHotPath:
     backward(): moe_combine_bwd -> moe_expert_bwd (routed, then shared) -> moe_combine (unit weights)
                 -> moe_route_bwd (gradient of the router logits)
     No arithmetic happens here; tensors are only allocated and handed to the library.
+
+    The shared experts depend on nothing the routed experts produce, so with overlap_shared their
+    calls go to a second stream of the same (default) priority and join before the combine: their
+    blocks then fill the CUs that the tail of a routed launch leaves idle (about 1 % of a step on the
+    DeepSeek-V3-shaped workload; off by default because per-kernel durations then overlap).
     """
 
-    def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0"):
+    def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0",
+                 overlap_shared: bool = False):
         self.shape, self.S, self.Fs, self.device = shape, n_shared, d_ff_shared, torch.device(device)
+        self.overlap = bool(overlap_shared and n_shared)
         s, dt, dev = shape, shape.torch_dtype, self.device
         A = s.T * s.k
         i32 = dict(dtype=torch.int32, device=dev)
@@ -269,15 +276,39 @@ class MoEHotPath:
             ws = max(ws, moe_expert_fwd_workspace_bytes(self.sshape, S, s.T, True),
                      moe_expert_bwd_workspace_bytes(self.sshape, S, s.T, True))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
+        self.ws_shared = self.ws
+        if self.overlap:  # concurrent calls need a workspace each
+            self.ws_shared = torch.empty(max(moe_expert_fwd_workspace_bytes(self.sshape, n_shared, s.T, True),
+                                             moe_expert_bwd_workspace_bytes(self.sshape, n_shared, s.T, True)),
+                                         dtype=torch.uint8, device=dev)
+            self.side = torch.cuda.Stream(device=dev)
+            self.ev_fork, self.ev_join = torch.cuda.Event(), torch.cuda.Event()
+
+    def _fork(self, stream):
+        """The side stream starts after everything already queued on the main stream."""
+        main = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self.ev_fork.record(main)
+        self.side.wait_event(self.ev_fork)
+        return main
+
+    def _join(self, main):
+        self.ev_join.record(self.side)
+        main.wait_event(self.ev_join)
 
     def forward(self, logits, X, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, stream=None):
         s, b = self.shape, self.b
         A = s.T * s.k
         self._logits = logits  # the gate's backward reads them again
+        if self.overlap:
+            main = self._fork(stream)
+            moe_expert_fwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], b["Ysh"],
+                           self.ws_shared, self.side)
         moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
         moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
         moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
-        if self.S:
+        if self.overlap:
+            self._join(main)
+        elif self.S:
             moe_expert_fwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], b["Ysh"],
                            self.ws, stream)
         moe_combine(s, b["Yp"], b["row_of"], b["topk_w"], b["Ysh"] if self.S else None, b["Y"], stream)
@@ -286,10 +317,16 @@ class MoEHotPath:
     def backward(self, dY, X, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, stream=None):
         s, b = self.shape, self.b
         A = s.T * s.k
+        if self.overlap:
+            main = self._fork(stream)
+            moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
+                           b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws_shared, self.side)
         moe_combine_bwd(s, dY, b["Yp"], b["row_of"], b["topk_w"], b["dYp"], b["dw"], stream)
         moe_expert_bwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["dYp"], b["dXp"],
                        b["active_ids"], b["n_active"], b["dWg_c"], b["dWu_c"], b["dWd_c"], self.ws, stream)
-        if self.S:
+        if self.overlap:
+            self._join(main)
+        elif self.S:
             moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
                            b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws, stream)
         moe_combine(s, b["dXp"], b["row_of"], None, b["dXsh"] if self.S else None, b["dX"], stream)

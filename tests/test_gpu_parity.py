@@ -205,6 +205,26 @@ def test_route_bwd(E, k, gate, renorm):
     assert scale_rel_err(out.cpu(), ref) <= 1e-4
 
 
+def test_overlap_shared_is_identical():
+    """Shared experts on a second stream: bit-identical to the single-stream order."""
+    import paper_2502_02581_amd as moe
+
+    cfg = small_cfg("ovl", T=700, d=256, E=4, k=2, d_ff=256, dtype="bf16", zipf_s=0.8, n_shared=2, d_ff_shared=192)
+    p = problem(cfg)
+    g = {k: v.cuda() for k, v in p.items()}
+    shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
+    outs = []
+    for overlap in (False, True):
+        hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, "cuda:0", overlap_shared=overlap)
+        for _ in range(3):  # repeated steps reuse the buffers and the events
+            hp.forward(g["logits"], g["X"], g["Wg"], g["Wu"], g["Wd"], g["Wsg"], g["Wsu"], g["Wsd"])
+            hp.backward(g["dY"], g["X"], g["Wg"], g["Wu"], g["Wd"], g["Wsg"], g["Wsu"], g["Wsd"])
+        torch.cuda.synchronize()
+        outs.append({k: hp.b[k].cpu() for k in ("Y", "dX", "dw", "dlogits", "dWsg", "dWsu", "dWsd", "Ysh", "dXsh")})
+    for k in outs[0]:
+        assert torch.equal(outs[0][k], outs[1][k]), k
+
+
 def test_determinism():
     """Two runs give bit-identical outputs, floating point included (no atomics on fp data)."""
     cfg = wl.scaled(wl.CONFIGS["stress"], T=1024, d=128, d_ff=96)
