@@ -24,6 +24,9 @@
  *    and moe_last_error() describes the reason (thread-local, host string).
  *  - Calls on one stream are ordered; two calls that share a workspace must not
  *    overlap.
+ *  - Empty inputs are valid: with T == 0 (n_rows == 0 for the expert calls) a call succeeds,
+ *    tensors with no elements may be null, and only the outputs that do not depend on tokens
+ *    are written (counts and offsets = 0; n_active = 0, active_ids = -1).
  */
 #ifndef MOE_HIP_H
 #define MOE_HIP_H

@@ -162,7 +162,8 @@ extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32
   using namespace moe;
   int rc = check_shape(shape, "moe_dispatch");
   if (rc) return rc;
-  if (!topk_idx || !counts || !offsets || !row_of || !src_of || !ws || (shape->T > 0 && (!X || !Xp))) {
+  // with T == 0 only counts and offsets are written (zeros); the per-assignment arrays may be null
+  if (!counts || !offsets || !ws || (shape->T > 0 && (!topk_idx || !row_of || !src_of || !X || !Xp))) {
     set_error("moe_dispatch: null pointer");
     return MOE_EINVAL;
   }

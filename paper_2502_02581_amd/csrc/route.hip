@@ -163,11 +163,11 @@ extern "C" int moe_route_bwd(const moe_shape_t* shape, const float* logits, cons
   using namespace moe;
   int rc = check_shape(shape, "moe_route_bwd");
   if (rc) return rc;
+  if (shape->T == 0) return MOE_OK;  // nothing to do (empty tensors may be null)
   if (!logits || !topk_idx || !dw || !dlogits) {
     set_error("moe_route_bwd: null pointer");
     return MOE_EINVAL;
   }
-  if (shape->T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   dim3 grid((shape->T + 3) / 4), block(256);
   const int E = shape->E;
@@ -189,11 +189,11 @@ extern "C" int moe_route(const moe_shape_t* shape, const float* logits, int32_t*
   using namespace moe;
   int rc = check_shape(shape, "moe_route");
   if (rc) return rc;
+  if (shape->T == 0) return MOE_OK;  // nothing to do (empty tensors may be null)
   if (!logits || !topk_idx || !topk_w) {
     set_error("moe_route: null pointer");
     return MOE_EINVAL;
   }
-  if (shape->T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   dim3 grid((shape->T + 3) / 4), block(256);
   const int E = shape->E;

@@ -239,6 +239,29 @@ def test_determinism():
             assert torch.equal(v, b[k]), k
 
 
+def test_empty_batch():
+    """T = 0: every call succeeds, counts/offsets/n_active are written (zeros), nothing else is touched."""
+    import paper_2502_02581_amd as moe
+
+    for dtype in ("f32", "bf16"):
+        cfg = small_cfg("empty", T=0, d=64, E=5, k=2, d_ff=64, dtype=dtype, n_shared=1, d_ff_shared=64)
+        W = wl.make_weights(cfg, "cuda")
+        shape = moe.MoEShape(0, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
+        hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, "cuda:0")
+        for key in ("counts", "offsets", "n_active", "active_ids"):
+            hp.b[key].fill_(77)
+        hp.b["dWg_c"].fill_(3.0)
+        x = torch.empty(0, cfg.d, dtype=shape.torch_dtype, device="cuda")
+        lg = torch.empty(0, cfg.E, device="cuda")
+        y = hp.forward(lg, x, W["Wg"], W["Wu"], W["Wd"], W["Wsg"], W["Wsu"], W["Wsd"])
+        dx = hp.backward(x, x, W["Wg"], W["Wu"], W["Wd"], W["Wsg"], W["Wsu"], W["Wsd"])
+        torch.cuda.synchronize()
+        assert y.shape == (0, cfg.d) and dx.shape == (0, cfg.d)
+        assert not hp.b["counts"].any() and not hp.b["offsets"].any()
+        assert int(hp.b["n_active"].item()) == 0 and bool((hp.b["active_ids"] == -1).all())
+        assert bool((hp.b["dWg_c"] == 3.0).all())  # no expert is active: no gradient slot is written
+
+
 def test_error_paths_launch_nothing():
     import paper_2502_02581_amd as moe
 
