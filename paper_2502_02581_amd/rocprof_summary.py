@@ -5,7 +5,10 @@
     python -m paper_2502_02581_amd.rocprof_summary traffic <fetch counter csv> <write counter csv> <out.txt>
                                                            --probe-bytes N --cmd "<command>"
 
+    python -m paper_2502_02581_amd.rocprof_summary counters <out.md> <counter csv>... --cmd "<command>" [--cmd ...]
+
 `stats` keeps the per-kernel call count and durations of a `--kernel-trace --stats` run.
+`counters` sums every collected counter per kernel and adds MFMA-busy and LDS ratios.
 `traffic` takes two `--pmc` runs of the same command (FETCH_SIZE, then WRITE_SIZE), averages each
 counter per dispatch and per kernel, and scales it to bytes with what the same counter reads for
 the library's copy_probe_kernel, which moves exactly --probe-bytes bytes each way.
@@ -71,6 +74,40 @@ def traffic(args):
             f.write(f"{fetch[k][1]}\t{fb:.0f}\t{wb:.0f}\t{fb + wb:.0f}\t{short_name(k)}\n")
 
 
+def counters(args):
+    """Per-kernel sums of whatever counters a --pmc run collected, plus the ratios they allow."""
+    tot = collections.defaultdict(lambda: collections.defaultdict(float))
+    for path in args.csv:
+        for r in csv.DictReader(open(path)):
+            if "moe::" not in r["Kernel_Name"]:
+                continue
+            k = short_name(r["Kernel_Name"])
+            tot[k][r["Counter_Name"]] += float(r["Counter_Value"])
+    with open(args.out, "w") as f:
+        f.write("# rocprofv3 --pmc counter sums per kernel (all dispatches of the run)\n\nCommands (from the repo root on one MI355X):\n\n")
+        for c in args.cmd:
+            f.write(f"    {c}\n")
+        f.write("\nDerived: MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES); executed bf16 MFMA FLOPs = "
+                "512 x SQ_INSTS_VALU_MFMA_MOPS_BF16 (padding rows of ragged tiles included); LDS bank conflict share = "
+                "SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE; LDS wait share = SQ_WAIT_INST_LDS / SQ_WAVE_CYCLES.\n\n")
+        for k in sorted(tot, key=lambda k: -tot[k].get("SQ_BUSY_CU_CYCLES", tot[k].get("SQ_WAVE_CYCLES", 0.0))):
+            v = tot[k]
+            if not any(c.startswith("SQ_") for c in v):
+                continue
+            f.write(f"`{k}`\n\n")
+            for c in sorted(v):
+                f.write(f"    {c:34s} {v[c]:.4g}\n")
+            if v.get("SQ_BUSY_CU_CYCLES") and "SQ_VALU_MFMA_BUSY_CYCLES" in v:
+                f.write(f"    MFMA busy                          {v['SQ_VALU_MFMA_BUSY_CYCLES'] / (4 * v['SQ_BUSY_CU_CYCLES']):.3f}\n")
+            if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in v:
+                f.write(f"    executed bf16 MFMA TFLOP           {512 * v['SQ_INSTS_VALU_MFMA_MOPS_BF16'] / 1e12:.3f}\n")
+            if v.get("SQ_LDS_IDX_ACTIVE") and "SQ_LDS_BANK_CONFLICT" in v:
+                f.write(f"    LDS bank conflict share            {v['SQ_LDS_BANK_CONFLICT'] / v['SQ_LDS_IDX_ACTIVE']:.3f}\n")
+            if v.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_LDS" in v:
+                f.write(f"    LDS wait share                     {v['SQ_WAIT_INST_LDS'] / v['SQ_WAVE_CYCLES']:.3f}\n")
+            f.write("\n")
+
+
 def read_traffic(path):
     """{kernel name: bytes per launch (fetched + written)} from a file written by `traffic`."""
     out = {}
@@ -97,6 +134,11 @@ def main():
     t.add_argument("--probe-bytes", type=int, required=True)
     t.add_argument("--cmd", required=True)
     t.set_defaults(fn=traffic)
+    c = sub.add_parser("counters")
+    c.add_argument("out")
+    c.add_argument("csv", nargs="+")
+    c.add_argument("--cmd", action="append", required=True)
+    c.set_defaults(fn=counters)
     args = ap.parse_args()
     args.fn(args)
 
