@@ -278,6 +278,7 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
   }
 #ifdef MOE_TRACE
   const unsigned long long t_start = (unsigned long long)wall_clock64();
+  const unsigned long long c_start = (unsigned long long)clock64();
 #endif
   if (CoreSet::kKinds == 1) {
     row_gemm_tile<Core0, NB, EPI, B_KC>(p, t, nt, smem);
@@ -290,7 +291,9 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
     }
   }
 #ifdef MOE_TRACE
-  trace_put(EPI | (NB << 4) | ((int)B_KC << 8), t.group, nt | (tile_kind(t) << 8) | (tile_rows(t) << 16), t_start);
+  // the group field carries the shader clock cycles of the tile (shader clock = cycles / wall time)
+  trace_put(EPI | (NB << 4) | ((int)B_KC << 8), (int)((unsigned long long)clock64() - c_start),
+            nt | (tile_kind(t) << 8) | (tile_rows(t) << 16), t_start);
 #endif
 }
 
