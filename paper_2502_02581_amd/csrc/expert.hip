@@ -385,9 +385,6 @@ static int pick_path(const moe_shape_t* s) {
   if (s->dtype == MOE_F32) return PATH_F32;
   return (s->d % 64 == 0 && s->d_ff % 64 == 0) ? PATH_BF16_DMA : PATH_BF16;
 }
-static int path_bm(int path) {
-  return path == PATH_F32 ? Cores<PATH_F32>::BM : path == PATH_BF16 ? Cores<PATH_BF16>::BM : Cores<PATH_BF16_DMA>::BM;
-}
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -439,7 +436,6 @@ struct FwdArgs {
 
 template <int PATH>
 static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
-  typedef Cores<PATH> C;
   const bool shared = a.offsets == nullptr;
   const int max_tiles = max_row_tiles(a.n_groups, a.n_rows, shared, plan_bm<PATH>());
   Plan pl = carve_plan(a.ws, a.n_groups, max_tiles);
@@ -552,7 +548,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
 }
 
-static size_t plan_size_for(const moe_shape_t* s, int n_groups, int n_rows, bool shared) {
+static size_t plan_size_for(int n_groups, int n_rows, bool shared) {
   // sized for the smallest row tile of any path, so the query does not depend on the path taken
   const int bound = max_row_tiles(n_groups, n_rows, shared, 64) + max_row_tiles(n_groups, n_rows, shared, 0);
   return align_up(plan_bytes(n_groups, bound + 1), 256);
@@ -574,7 +570,7 @@ extern "C" size_t moe_expert_fwd_workspace_bytes(const moe_shape_t* shape, int32
                                                  int32_t shared) {
   using namespace moe;
   if (!shape || n_groups < 1 || n_rows < 0) return 0;
-  return plan_size_for(shape, n_groups, n_rows, shared != 0);
+  return plan_size_for(n_groups, n_rows, shared != 0);
 }
 
 // plan + dG + dU ([n_rows, d_ff] each; shared mode keeps them per group)
@@ -583,7 +579,7 @@ extern "C" size_t moe_expert_bwd_workspace_bytes(const moe_shape_t* shape, int32
   using namespace moe;
   if (!shape || n_groups < 1 || n_rows < 0) return 0;
   const size_t rows = (size_t)(shared ? n_groups : 1) * (size_t)n_rows;
-  return plan_size_for(shape, n_groups, n_rows, shared != 0) +
+  return plan_size_for(n_groups, n_rows, shared != 0) +
          2 * align_up(rows * shape->d_ff * elem_size(shape->dtype), 256);
 }
 
@@ -643,7 +639,7 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
     return MOE_EWS;
   }
   BwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xin, Wg, Wu, Wd, G, U, H, dYin, dXin,
-               active_ids, n_active, dWg_c, dWu_c, dWd_c, ws, plan_size_for(shape, n_groups, n_rows, offsets == nullptr)};
+               active_ids, n_active, dWg_c, dWu_c, dWd_c, ws, plan_size_for(n_groups, n_rows, offsets == nullptr)};
   switch (pick_path(shape)) {
     case PATH_F32: expert_bwd_impl<PATH_F32>(a, (hipStream_t)stream); break;
     case PATH_BF16: expert_bwd_impl<PATH_BF16>(a, (hipStream_t)stream); break;

@@ -569,9 +569,10 @@ struct MfmaDmaCore {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    // One wave per SIMD issues in order and a tile load stalls its wave for as long as the texture
-    // addresser is busy with earlier loads (16 cycles per load and wave), so every overlap has to
-    // be in the instruction stream itself.  Per K iteration t (4 k-steps of kMfma MFMAs):
+    // A wave issues in order and a tile load holds it for as long as the memory pipeline has no
+    // free slot, so the overlap of loads, LDS reads and MFMAs is written into the instruction
+    // stream itself (the second wave of the SIMD fills what is left).  Per K iteration t (4 k-steps
+    // of kMfma MFMAs):
     //   - the fragments of k-step ks+1 are read from LDS during the MFMAs of ks, one per MFMA;
     //   - the loads of B(t+1), then of A(t+2), are spread evenly between the MFMAs;
     //   - half-way through the last k-step all LDS reads of this iteration are done: wait until

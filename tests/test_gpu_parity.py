@@ -98,6 +98,25 @@ LAYER_CASES = [
 ]
 
 
+# odd multiples of 64 in d and d_ff (ragged last column tile and K counts that are not a multiple of the
+# pipeline depth), a single token, fewer tokens than experts, shared experts of another width
+SWEEP = [
+    small_cfg("sw-1tok", T=1, d=64, E=4, k=2, d_ff=192, dtype="bf16"),
+    small_cfg("sw-77", T=77, d=192, E=7, k=3, d_ff=64, dtype="bf16", zipf_s=1.0, gate="sigmoid"),
+    small_cfg("sw-513", T=513, d=320, E=5, k=2, d_ff=448, dtype="bf16", zipf_s=0.7, n_shared=1, d_ff_shared=192),
+    small_cfg("sw-wide", T=300, d=448, E=3, k=1, d_ff=320, dtype="bf16", zipf_s=2.0),
+    small_cfg("sw-k1tail", T=260, d=576, E=2, k=2, d_ff=128, dtype="bf16", renorm=False),
+    small_cfg("sw-fewtok", T=5, d=128, E=16, k=4, d_ff=128, dtype="bf16", n_shared=2, d_ff_shared=64),
+]
+
+
+@pytest.mark.parametrize("cfg", SWEEP, ids=lambda c: c.name)
+def test_dma_path_shape_sweep(cfg):
+    p = problem(cfg, unit_scale=True)
+    errs = compare_layer(cfg, run_gpu(cfg, p), run_oracle(cfg, p))
+    print(cfg.name, {k: f"{v:.2e}" for k, v in errs.items()})
+
+
 @pytest.mark.parametrize("cfg,unit", LAYER_CASES, ids=lambda v: v.name if hasattr(v, "name") else str(v))
 def test_layer_parity_small(cfg, unit):
     if cfg.routing == "stress":
