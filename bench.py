@@ -209,11 +209,12 @@ def main():
     dom_n, dom_ms = prof[dom]
     peak = MFMA_BF16_PEAK_TF if cfg.dtype == "bf16" else FP32_VEC_PEAK_TF
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": dom, "symbol": SYMBOL[dom],
+    dma_path = cfg.dtype == "bf16" and cfg.d % 64 == 0 and cfg.d_ff % 64 == 0   # SYMBOL names that path's kernels
+    roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": dom, "symbol": SYMBOL[dom] if dma_path else None,
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
                 "flop_per_launch_avg": flops[dom] * args.steps / dom_n,
-                "traffic": measured_traffic(cfg.name, SYMBOL[dom]) if cfg.dtype == "bf16" else None}
+                "traffic": measured_traffic(cfg.name, SYMBOL[dom]) if dma_path else None}
 
     out = {
         "metric": "moe_layer_fwd_bwd_tokens_per_s", "value": round(cfg.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
