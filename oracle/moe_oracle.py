@@ -21,6 +21,8 @@ open are taken as follows (each is a choice of this build, not of the paper):
     assignment index a = t*k + j.
   * shared experts are always-on experts of weight 1, summed into the output
     (Eq. 2: experts summed along d_ff).
+  * the gating network that produces the logits (router_fwd / router_bwd) is one
+    linear map without bias; the paper only calls it "lightweight".
 Every function works in the real type R (float64 unless told otherwise) on the
 input values widened to R; no intermediate is rounded to a narrower type.
 
@@ -35,6 +37,24 @@ from __future__ import annotations
 import numpy as np
 
 DEFAULT_R = np.float64
+
+
+# --------------------------------------------------------------------------- router
+def router_fwd(X, Wr, R=DEFAULT_R):
+    """Logits of the gating network g of Eq. 3, read as one linear map of the token:
+    logits[t, e] = sum_c X[t, c] * Wr[c, e]   (X [T, d], Wr [d, E])."""
+    return np.asarray(X).astype(R) @ np.asarray(Wr).astype(R)
+
+
+def router_bwd(X, Wr, dlogits, R=DEFAULT_R):
+    """Adjoint of router_fwd: dWr[c, e] = sum_t X[t, c] dlogits[t, e];  dX[t, c] = sum_e dlogits[t, e] Wr[c, e]."""
+    X = np.asarray(X).astype(R)
+    Wr = np.asarray(Wr).astype(R)
+    dl = np.asarray(dlogits).astype(R)
+    dWr = np.zeros_like(Wr)
+    for t in range(X.shape[0]):
+        dWr += np.outer(X[t], dl[t])
+    return dl @ Wr.T, dWr
 
 
 # --------------------------------------------------------------------------- gating

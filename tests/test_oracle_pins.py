@@ -372,6 +372,41 @@ def _pins_pass():
     return True
 
 
+def test_router_linear_map_closed_form_and_autograd():
+    """router_fwd / router_bwd: a hand-worked 2x2 case, then torch autograd on a random case."""
+    X = np.array([[1.0, 2.0], [-1.0, 0.5]])
+    Wr = np.array([[3.0, -1.0, 0.0], [0.5, 2.0, 1.0]])
+    np.testing.assert_array_equal(orc.router_fwd(X, Wr), np.array([[4.0, 3.0, 2.0], [-2.75, 2.0, 0.5]]))
+    dl = np.array([[1.0, 0.0, -1.0], [2.0, 1.0, 0.0]])
+    dX, dWr = orc.router_bwd(X, Wr, dl)
+    np.testing.assert_array_equal(dX, np.array([[3.0, -0.5], [5.0, 3.0]]))
+    np.testing.assert_array_equal(dWr, np.array([[-1.0, -1.0, -1.0], [3.0, 0.5, -2.0]]))
+    rng = np.random.default_rng(3)
+    X, Wr, dl = rng.normal(size=(13, 7)), rng.normal(size=(7, 5)), rng.normal(size=(13, 5))
+    tx = torch.tensor(X, requires_grad=True)
+    tw = torch.tensor(Wr, requires_grad=True)
+    lg = tx @ tw
+    np.testing.assert_allclose(orc.router_fwd(X, Wr), lg.detach().numpy(), rtol=1e-13, atol=1e-13)
+    (lg * torch.tensor(dl)).sum().backward()
+    dX, dWr = orc.router_bwd(X, Wr, dl)
+    np.testing.assert_allclose(dX, tx.grad.numpy(), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dWr, tw.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_planted_mistake_in_router_is_caught(monkeypatch):
+    real = orc.router_bwd
+
+    def transposed(X, Wr, dlogits, R=np.float64):
+        dX, dWr = real(X, Wr, dlogits, R)
+        return dX, (np.asarray(dlogits).T @ np.asarray(X)).T[::-1]  # rows of dWr reversed
+
+    with monkeypatch.context() as m:
+        m.setattr(orc, "router_bwd", transposed)
+        with pytest.raises(AssertionError):
+            test_router_linear_map_closed_form_and_autograd()
+    test_router_linear_map_closed_form_and_autograd()
+
+
 def test_planted_mistakes_are_caught(monkeypatch):
     assert _pins_pass()
     real = {n: getattr(orc, n) for n in ("silu", "swiglu_ffn_bwd", "combine", "combine_bwd", "dispatch_plan",
