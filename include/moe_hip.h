@@ -78,6 +78,23 @@ size_t moe_expert_bwd_workspace_bytes(const moe_shape_t* shape, int32_t n_groups
                                       int32_t shared);
 
 /*
+ * moe_router_fwd / moe_router_bwd -- the gating network that produces the logits of Eq. 3, read
+ * as one linear map without bias (the paper only calls it lightweight), and its adjoint:
+ *   logits = X Wr;      dWr = X^T dlogits;   dX = dlogits Wr^T  (added to dX when accumulate != 0).
+ *   X [T, d], Wr [d, E], dWr [d, E], dX [T, d] in shape->dtype; logits, dlogits [T, E] f32.
+ * bf16 operands, fp32 accumulation; dlogits is rounded to bf16 for the two backward products.
+ * E need not be a multiple of anything: the GEMMs run on zero-padded copies in the workspace
+ * (moe_router_*_workspace_bytes, host computation).  With T == 0, moe_router_bwd writes dWr = 0.
+ * These calls are not part of the path the benchmark times (logits are an input there).
+ */
+size_t moe_router_fwd_workspace_bytes(const moe_shape_t* shape);
+size_t moe_router_bwd_workspace_bytes(const moe_shape_t* shape);
+int moe_router_fwd(const moe_shape_t* shape, const void* X, const void* Wr, float* logits, void* ws, size_t ws_bytes,
+                   void* stream);
+int moe_router_bwd(const moe_shape_t* shape, const void* X, const void* Wr, const float* dlogits, void* dWr, void* dX,
+                   int32_t accumulate, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * moe_route -- the gate of Eq. 3: g(x) and argtopk.
  *   logits   [T, E] f32  router logits
  *   topk_idx [T, k] i32  out: the k experts of each token, by descending logit; equal

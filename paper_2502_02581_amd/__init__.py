@@ -6,9 +6,11 @@ memory and streams.  There is no CPU or PyTorch fallback: a missing library is a
 """
 from .binding import (MoEShape, MoEHotPath, lib_path, load_library, moe_abi_version, moe_combine, moe_combine_bwd,
                       moe_dispatch, moe_dispatch_workspace_bytes, moe_expert_bwd, moe_expert_bwd_workspace_bytes,
-                      moe_expert_fwd, moe_expert_fwd_workspace_bytes, moe_last_error, moe_route, moe_route_bwd, MoEError,
+                      moe_expert_fwd, moe_expert_fwd_workspace_bytes, moe_last_error, moe_route, moe_route_bwd, MoEError, moe_router_fwd, moe_router_bwd,
+                      moe_router_fwd_workspace_bytes, moe_router_bwd_workspace_bytes,
                       moe_profile_enable, moe_profile_report, moe_copy_probe)
 
 __all__ = ["MoEShape", "MoEHotPath", "MoEError", "lib_path", "load_library", "moe_abi_version", "moe_last_error",
-           "moe_route", "moe_route_bwd", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine", "moe_combine_bwd",
+           "moe_route", "moe_route_bwd", "moe_router_fwd", "moe_router_bwd", "moe_router_fwd_workspace_bytes",
+           "moe_router_bwd_workspace_bytes", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd", "moe_combine", "moe_combine_bwd",
            "moe_profile_enable", "moe_profile_report", "moe_copy_probe", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes", "moe_expert_bwd_workspace_bytes"]

@@ -14,7 +14,8 @@ _lib = None
 
 MOE_F32, MOE_BF16 = 0, 1
 MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
-EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
+EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd", "moe_router_bwd",
+           "moe_router_fwd_workspace_bytes", "moe_router_bwd_workspace_bytes", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe"]
 
@@ -74,6 +75,13 @@ def load_library():
         f.argtypes = [shp, i32, i32, i32]
     lib.moe_route.restype = ctypes.c_int
     lib.moe_route.argtypes = [shp, vp, vp, vp, vp]
+    for f in (lib.moe_router_fwd_workspace_bytes, lib.moe_router_bwd_workspace_bytes):
+        f.restype = sz
+        f.argtypes = [shp]
+    lib.moe_router_fwd.restype = ctypes.c_int
+    lib.moe_router_fwd.argtypes = [shp, vp, vp, vp, vp, sz, vp]
+    lib.moe_router_bwd.restype = ctypes.c_int
+    lib.moe_router_bwd.argtypes = [shp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.moe_route_bwd.restype = ctypes.c_int
     lib.moe_route_bwd.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.moe_dispatch.restype = ctypes.c_int
@@ -144,6 +152,31 @@ def moe_route(shape: MoEShape, logits, topk_idx, topk_w, stream=None):
                                   _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"),
                                   _stream(stream))
     _check(rc, "moe_route")
+
+
+def moe_router_fwd_workspace_bytes(shape: MoEShape) -> int:
+    return int(load_library().moe_router_fwd_workspace_bytes(ctypes.byref(shape.c())))
+
+
+def moe_router_bwd_workspace_bytes(shape: MoEShape) -> int:
+    return int(load_library().moe_router_bwd_workspace_bytes(ctypes.byref(shape.c())))
+
+
+def moe_router_fwd(shape: MoEShape, X, Wr, logits, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_router_fwd(ctypes.byref(shape.c()), _ptr(X, dt, "X"), _ptr(Wr, dt, "Wr"),
+                                       _ptr(logits, torch.float32, "logits"), _ptr(ws, None, "ws"),
+                                       ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_router_fwd")
+
+
+def moe_router_bwd(shape: MoEShape, X, Wr, dlogits, dWr, dX, accumulate: bool, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_router_bwd(ctypes.byref(shape.c()), _ptr(X, dt, "X"), _ptr(Wr, dt, "Wr"),
+                                       _ptr(dlogits, torch.float32, "dlogits"), _ptr(dWr, dt, "dWr"), _ptr(dX, dt, "dX"),
+                                       int(bool(accumulate)), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(),
+                                       _stream(stream))
+    _check(rc, "moe_router_bwd")
 
 
 def moe_route_bwd(shape: MoEShape, logits, topk_idx, dw, dlogits, stream=None):

@@ -161,7 +161,7 @@ template <int W> struct Pack<bf16_t, W> {
   }
 };
 
-enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2 };
+enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_STORE_F32 = 3, EPI_ADD = 4 };
 
 __device__ __forceinline__ uint32_t clip_u32(int64_t v) {
   return v < 0 ? 0u : v > 0xffffffffll ? 0xffffffffu : (uint32_t)v;
@@ -212,6 +212,14 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
     if (EPI == EPI_STORE) {
       Pack<T, W>::store((T*)p.out[0] + off, v[0]);
+    } else if (EPI == EPI_STORE_F32) {  // fp32 output whatever the operand type (router logits)
+      Pack<float, W>::store((float*)p.out[0] + off, v[0]);
+    } else if (EPI == EPI_ADD) {        // accumulate into the output
+      float o[W];
+      Pack<T, W>::load((const T*)p.out[0] + off, o);
+#pragma unroll
+      for (int q = 0; q < W; q++) o[q] += v[0][q];
+      Pack<T, W>::store((T*)p.out[0] + off, o);
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[W];
 #pragma unroll
@@ -270,10 +278,14 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
     if (mt >= *p.n_tiles) return;
     t = p.tiles[mt];
   } else {
+    // direct tiling: tiles of one height (on the LDS-DMA path the caller may pick a shorter kind, so
+    // that a GEMM with few column tiles still fills the chip)
+    const int kind = CoreSet::kKinds == 4 ? p.direct_kind : 0;
+    const int bm = CoreSet::kKinds == 4 ? kind_height(kind) : Core0::BM;
     t.group = 0;
-    t.row0_in = mt * Core0::BM;
+    t.row0_in = mt * bm;
     if (t.row0_in >= p.n_rows) return;
-    t.rows = min(Core0::BM, p.n_rows - t.row0_in);
+    t.rows = min(bm, p.n_rows - t.row0_in) | (kind << 16);
     t.row0_out = t.row0_in;
   }
 #ifdef MOE_TRACE
@@ -303,7 +315,8 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   typedef typename Core::T T;
   extern __shared__ __align__(16) char smem[];
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
-  const int4 gi = p.ginfo[blockIdx.y];  // {group, rows, first row, compact slot}
+  // {group, rows, first row, compact slot}; without records every group has n_rows rows and its own slot
+  const int4 gi = p.ginfo ? p.ginfo[blockIdx.y] : make_int4((int)blockIdx.y, p.n_rows, 0, (int)blockIdx.y);
   const int g = gi.x, K = gi.y, start = gi.z, slot = gi.w;
   if (K <= 0 || K < p.k_min || K > p.k_max) return;
   // single-product kernels serve the two products of a dual GEMM through blockIdx.z
@@ -400,7 +413,7 @@ template <class CoreSet, int NB, int EPI, bool B_KC>
 static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipStream_t st) {
   typedef typename CoreSet::template tile<0> Core;
   const int ntn = ceil_div(p.N, Core::BN);
-  const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, Core::BM);
+  const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, CoreSet::kKinds == 4 ? kind_height(p.direct_kind) : Core::BM);
   if (n_mt == 0 || ntn == 0) return;
   auto kern = row_gemm_kernel<CoreSet, NB, EPI, B_KC>;
   static bool attr_done = false;
@@ -646,6 +659,182 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
     default: expert_bwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
   }
   return launch_status("moe_expert_bwd");
+}
+
+// ------------------------------------------------------------------------------------ router
+// The gating network read as one linear map: logits = X Wr, and its adjoint.  E is arbitrary, so
+// the GEMMs run on copies padded to Ep = E rounded up to 64 columns (zeros), which live in the
+// workspace; when E is already a multiple of 64 the caller's buffers are used directly.
+namespace moe {
+
+template <typename TI, typename TO>
+__device__ __forceinline__ TO cvt_elem(TI v);
+template <> __device__ __forceinline__ float cvt_elem<float, float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t cvt_elem<bf16_t, bf16_t>(bf16_t v) { return v; }
+template <> __device__ __forceinline__ bf16_t cvt_elem<float, bf16_t>(float v) { return f32_to_bf16(v); }
+
+// dst[r][c] = c < cols_in ? src[r][c] : 0 for c < cols_out (cols_out >= cols_in: pad; the other way: strip)
+template <typename TI, typename TO>
+__global__ __launch_bounds__(256) void recolumn_kernel(const TI* __restrict__ src, TO* __restrict__ dst, int64_t rows,
+                                                       int cols_in, int cols_out) {
+  const int64_t n = rows * cols_out;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / cols_out;
+    const int c = (int)(i - r * cols_out);
+    dst[i] = c < cols_in ? cvt_elem<TI, TO>(src[r * cols_in + c]) : cvt_elem<TI, TO>(TI(0));
+  }
+}
+template <typename TI, typename TO>
+static void recolumn(const char* label, const void* src, void* dst, int64_t rows, int cols_in, int cols_out, hipStream_t st) {
+  const int64_t n = rows * cols_out;
+  if (n == 0) return;
+  ProfScope prof(label, st);
+  hipLaunchKernelGGL((recolumn_kernel<TI, TO>), dim3((unsigned)std::min<int64_t>((n + 255) / 256, 4096)), dim3(256), 0, st,
+                     (const TI*)src, (TO*)dst, rows, cols_in, cols_out);
+}
+
+static int router_path(const moe_shape_t* s) {
+  if (s->dtype == MOE_F32) return PATH_F32;
+  return s->d % 64 == 0 ? PATH_BF16_DMA : PATH_BF16;
+}
+static int padded_experts(const moe_shape_t* s) { return (s->E + 63) / 64 * 64; }
+
+template <int PATH>
+static void router_fwd_impl(const moe_shape_t* s, const void* X, const void* Wr, float* logits, char* ws, hipStream_t st) {
+  typedef typename Cores<PATH>::template core<1, true, false>::T T;
+  const int Ep = padded_experts(s);
+  const bool padded = Ep != s->E;
+  const void* B = Wr;
+  float* out = logits;
+  if (padded) {
+    T* WrP = (T*)ws;
+    out = (float*)(ws + align_up((size_t)s->d * Ep * sizeof(T), 256));
+    recolumn<T, T>("router_pad", Wr, WrP, s->d, s->E, Ep, st);
+    B = WrP;
+  }
+  RowGemm p = {};
+  p.n_rows = s->T; p.direct_kind = 2;  // 64-row tiles: E is small, so the rows have to fill the chip
+  p.N = Ep; p.K = s->d; p.n_pairs = 1; p.n_segs = 1;
+  p.A[0] = X; p.lda = s->d;
+  p.B[0] = B; p.ldb = Ep;
+  p.out[0] = out; p.ldc = Ep;
+  launch_row<RowCores<PATH, 1, false>, 1, EPI_STORE_F32, false>("gemm_router_fwd", p, 0, st);
+  if (padded) recolumn<float, float>("router_pad", out, logits, s->T, Ep, s->E, st);
+}
+
+template <int PATH>
+static void router_bwd_impl(const moe_shape_t* s, const void* X, const void* Wr, const float* dlogits, void* dWr, void* dX,
+                            bool accumulate, char* ws, hipStream_t st) {
+  typedef typename Cores<PATH>::template core<1, true, false>::T T;
+  typedef Cores<PATH> C;
+  const int Ep = padded_experts(s);
+  const bool padded = Ep != s->E;
+  // workspace: dlogits in the operand type [T, Ep]; then, when padded, Wr [d, Ep] and dWr [d, Ep]
+  T* dlP = (T*)ws;
+  char* q0 = ws + align_up((size_t)s->T * Ep * sizeof(T), 256);
+  T* WrP = (T*)q0;
+  T* dWrP = (T*)(q0 + align_up((size_t)s->d * Ep * sizeof(T), 256));
+  recolumn<float, T>("router_pad", dlogits, dlP, s->T, s->E, Ep, st);
+  const void* B = Wr;
+  void* dW = dWr;
+  if (padded) {
+    recolumn<T, T>("router_pad", Wr, WrP, s->d, s->E, Ep, st);
+    B = WrP;
+    dW = dWrP;
+  }
+  // dWr = X^T dlogits  (one group of T rows)
+  WGemm w = {};
+  w.ginfo = nullptr; w.n_rows = s->T;
+  w.M = s->d; w.N = Ep;
+  w.A = X; w.lda = s->d; w.a_per_group = 0;
+  w.B[0] = dlP; w.ldb = Ep; w.b_per_group = 0;
+  w.C[0] = dW; w.c_slot = (int64_t)s->d * Ep;
+  w.k_min = 1; w.k_max = 0x7fffffff;
+  launch_w<typename C::template core<1, false, false>, 1>("gemm_router_dw", w, 1, st);
+  if (padded) recolumn<T, T>("router_pad", dWrP, dWr, s->d, Ep, s->E, st);
+  // dX (+)= dlogits Wr^T
+  RowGemm p = {};
+  p.n_rows = s->T; p.direct_kind = 0;
+  p.N = s->d; p.K = Ep; p.n_pairs = 1; p.n_segs = 1;
+  p.A[0] = dlP; p.lda = Ep;
+  p.B[0] = B; p.ldb = Ep;
+  p.out[0] = dX; p.ldc = s->d;
+  if (accumulate) launch_row<RowCores<PATH, 1, true>, 1, EPI_ADD, true>("gemm_router_dx", p, 0, st);
+  else launch_row<RowCores<PATH, 1, true>, 1, EPI_STORE, true>("gemm_router_dx", p, 0, st);
+}
+
+}  // namespace moe
+
+extern "C" size_t moe_router_fwd_workspace_bytes(const moe_shape_t* shape) {
+  using namespace moe;
+  if (!shape || shape->E < 1 || shape->d < 1 || shape->T < 0) return 0;
+  const int Ep = padded_experts(shape);
+  if (Ep == shape->E) return 256;
+  return align_up((size_t)shape->d * Ep * elem_size(shape->dtype), 256) + align_up((size_t)shape->T * Ep * 4, 256);
+}
+
+extern "C" size_t moe_router_bwd_workspace_bytes(const moe_shape_t* shape) {
+  using namespace moe;
+  if (!shape || shape->E < 1 || shape->d < 1 || shape->T < 0) return 0;
+  const int Ep = padded_experts(shape);
+  const size_t es = elem_size(shape->dtype);
+  return align_up((size_t)shape->T * Ep * es, 256) + 2 * align_up((size_t)shape->d * Ep * es, 256);
+}
+
+extern "C" int moe_router_fwd(const moe_shape_t* shape, const void* X, const void* Wr, float* logits, void* ws,
+                              size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_router_fwd");
+  if (rc) return rc;
+  if (shape->T == 0) return MOE_OK;
+  if (!X || !Wr || !logits || !ws) {
+    set_error("moe_router_fwd: null pointer");
+    return MOE_EINVAL;
+  }
+  if (!aligned16(X) || !aligned16(Wr) || !aligned16(logits) || !aligned16(ws)) {
+    set_error("moe_router_fwd: every tensor must be 16-byte aligned");
+    return MOE_EINVAL;
+  }
+  if (ws_bytes < moe_router_fwd_workspace_bytes(shape)) {
+    set_error("moe_router_fwd: workspace of %zu bytes, need %zu", ws_bytes, moe_router_fwd_workspace_bytes(shape));
+    return MOE_EWS;
+  }
+  switch (router_path(shape)) {
+    case PATH_F32: router_fwd_impl<PATH_F32>(shape, X, Wr, logits, (char*)ws, (hipStream_t)stream); break;
+    case PATH_BF16: router_fwd_impl<PATH_BF16>(shape, X, Wr, logits, (char*)ws, (hipStream_t)stream); break;
+    default: router_fwd_impl<PATH_BF16_DMA>(shape, X, Wr, logits, (char*)ws, (hipStream_t)stream); break;
+  }
+  return launch_status("moe_router_fwd");
+}
+
+extern "C" int moe_router_bwd(const moe_shape_t* shape, const void* X, const void* Wr, const float* dlogits, void* dWr,
+                              void* dX, int32_t accumulate, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_router_bwd");
+  if (rc) return rc;
+  if (!Wr || !dWr || !ws || (shape->T > 0 && (!X || !dlogits || !dX))) {
+    set_error("moe_router_bwd: null pointer");
+    return MOE_EINVAL;
+  }
+  if (!aligned16(X) || !aligned16(Wr) || !aligned16(dlogits) || !aligned16(dWr) || !aligned16(dX) || !aligned16(ws)) {
+    set_error("moe_router_bwd: every tensor must be 16-byte aligned");
+    return MOE_EINVAL;
+  }
+  if (ws_bytes < moe_router_bwd_workspace_bytes(shape)) {
+    set_error("moe_router_bwd: workspace of %zu bytes, need %zu", ws_bytes, moe_router_bwd_workspace_bytes(shape));
+    return MOE_EWS;
+  }
+  if (shape->T == 0) {  // no tokens: the weight gradient is zero, there is no dX
+    if (shape->dtype == MOE_F32) recolumn<float, float>("router_pad", nullptr, dWr, shape->d, 0, shape->E, (hipStream_t)stream);
+    else recolumn<bf16_t, bf16_t>("router_pad", nullptr, dWr, shape->d, 0, shape->E, (hipStream_t)stream);
+    return launch_status("moe_router_bwd");
+  }
+  switch (router_path(shape)) {
+    case PATH_F32: router_bwd_impl<PATH_F32>(shape, X, Wr, dlogits, dWr, dX, accumulate != 0, (char*)ws, (hipStream_t)stream); break;
+    case PATH_BF16: router_bwd_impl<PATH_BF16>(shape, X, Wr, dlogits, dWr, dX, accumulate != 0, (char*)ws, (hipStream_t)stream); break;
+    default: router_bwd_impl<PATH_BF16_DMA>(shape, X, Wr, dlogits, dWr, dX, accumulate != 0, (char*)ws, (hipStream_t)stream); break;
+  }
+  return launch_status("moe_router_bwd");
 }
 
 #ifdef MOE_TRACE

@@ -45,6 +45,7 @@ struct RowGemm {
   const RowTile* tiles;     // NULL: direct tiling of n_rows rows, single group 0
   const int32_t* n_tiles;
   int32_t n_rows;
+  int32_t direct_kind;      // tiles == NULL on the LDS-DMA path: tile kind (height 256 >> kind) of the direct tiling
   int32_t N, K;
   int32_t n_pairs, n_segs;
   const void* A[2];         // per pair; element (row, k) at A + seg*a_seg + row*lda + k
@@ -62,7 +63,7 @@ struct RowGemm {
 
 // per group: C[M, N] = A_g^T B_g over the rows of the group (K = rows of the group)
 struct WGemm {
-  const int4* ginfo;        // per launch index (descending rows): {group, rows, first row, compact slot}
+  const int4* ginfo;        // per launch index (descending rows): {group, rows, first row, compact slot}; NULL: identity
   int32_t n_rows;
   int32_t M, N;
   const void* A;            // element (row, m) at A + row*lda + m

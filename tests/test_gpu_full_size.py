@@ -131,3 +131,36 @@ def test_full_size_sampled(name):
     print(name, {k: f"{v:.2e}" for k, v in errs.items()})
     bad = {k: v for k, v in errs.items() if not v <= TOL}
     assert not bad, f"{name}: over tolerance {TOL}: {bad}"
+
+
+@pytest.mark.parametrize("name", ["qwen", "dsv3"])
+def test_router_full_size_sampled(name):
+    """Router GEMMs at the full token count: sampled token rows of logits and dX, sampled rows of dWr."""
+    import paper_2502_02581_amd as moe
+
+    cfg = wl.CONFIGS[name]
+    T, d, E = cfg.T, cfg.d, cfg.E
+    g = torch.Generator().manual_seed(23)
+    X = wl.make_tokens(cfg, 1.0)
+    Wr = (torch.randn(d, E, generator=g) / d ** 0.5).to(torch.bfloat16)
+    dl = torch.randn(T, E, generator=g)
+    shape = moe.MoEShape(T, d, E, cfg.k, cfg.d_ff, "bf16")
+    dev = "cuda"
+    ws = torch.empty(max(moe.moe_router_fwd_workspace_bytes(shape), moe.moe_router_bwd_workspace_bytes(shape)),
+                     dtype=torch.uint8, device=dev)
+    logits = torch.empty(T, E, device=dev)
+    dWr = torch.empty(d, E, dtype=torch.bfloat16, device=dev)
+    dX = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+    Xg, Wg, dg = X.to(dev), Wr.to(dev), dl.to(dev)
+    moe.moe_router_fwd(shape, Xg, Wg, logits, ws)
+    moe.moe_router_bwd(shape, Xg, Wg, dg, dWr, dX, False, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, 62)]))
+    cols = np.unique(np.concatenate([[0, d - 1], rng.integers(0, d, 126)]))
+    X64, W64, dl64 = np64(X), np64(Wr), dl.numpy().astype(np.float64)
+    assert scale_rel_err(logits.cpu()[rows], orc.router_fwd(X64[rows], W64)) <= 1e-4
+    ref_dX, _ = orc.router_bwd(X64[rows], W64, dl64[rows])
+    assert scale_rel_err(dX.cpu()[rows], ref_dX) <= TOL
+    _, ref_dW = orc.router_bwd(X64[:, cols], W64[cols], dl64)   # rows `cols` of dWr depend on those columns of X only
+    assert scale_rel_err(dWr.cpu()[cols], ref_dW) <= TOL

@@ -224,6 +224,43 @@ def test_route_bwd(E, k, gate, renorm):
     assert scale_rel_err(out.cpu(), ref) <= 1e-4
 
 
+ROUTER_CASES = [
+    # (T, d, E, dtype): fp32 path; general bf16 path (d not a multiple of 64); LDS-DMA path with E
+    # not a multiple of 8, E a multiple of 64, E above one column tile
+    (70, 40, 6, "f32"), (300, 72, 60, "f32"), (130, 136, 12, "bf16"), (513, 192, 60, "bf16"),
+    (700, 256, 64, "bf16"), (1100, 448, 320, "bf16"), (1, 64, 1, "bf16"),
+]
+
+
+@pytest.mark.parametrize("T,d,E,dtype", ROUTER_CASES)
+def test_router_linear_map(T, d, E, dtype):
+    """logits = X Wr, dWr = X^T dlogits, dX (+)= dlogits Wr^T against the oracle."""
+    import paper_2502_02581_amd as moe
+
+    g = torch.Generator().manual_seed(17)
+    td = torch.float32 if dtype == "f32" else torch.bfloat16
+    X = torch.randn(T, d, generator=g).to(td)
+    Wr = (torch.randn(d, E, generator=g) / d ** 0.5).to(td)
+    dl = torch.randn(T, E, generator=g)
+    dX0 = torch.randn(T, d, generator=g).to(td)
+    shape = moe.MoEShape(T, d, E, 1, 64, dtype)
+    dev = "cuda"
+    ws = torch.empty(max(moe.moe_router_fwd_workspace_bytes(shape), moe.moe_router_bwd_workspace_bytes(shape)),
+                     dtype=torch.uint8, device=dev)
+    logits = torch.full((T, E), float("nan"), device=dev)
+    moe.moe_router_fwd(shape, X.to(dev), Wr.to(dev), logits, ws)
+    ref = orc.router_fwd(np64(X), np64(Wr))
+    assert scale_rel_err(logits.cpu(), ref) <= 1e-4  # fp32 output of exactly representable operands
+    tol = TOL[dtype]
+    ref_dX, ref_dWr = orc.router_bwd(np64(X), np64(Wr), dl.numpy())
+    for accumulate in (False, True):
+        dWr = torch.full((d, E), float("nan"), dtype=td, device=dev)
+        dX = dX0.to(dev).clone()
+        moe.moe_router_bwd(shape, X.to(dev), Wr.to(dev), dl.to(dev), dWr, dX, accumulate, ws)
+        assert scale_rel_err(dWr.cpu(), ref_dWr) <= tol
+        assert scale_rel_err(dX.cpu(), ref_dX + (np64(dX0) if accumulate else 0.0)) <= tol
+
+
 def test_overlap_shared_is_identical():
     """Shared experts on a second stream: bit-identical to the single-stream order."""
     import paper_2502_02581_amd as moe
