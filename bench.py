@@ -130,7 +130,7 @@ def verify(cfg, inp, weights, hp):
     return worst
 
 
-CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 96, "phi": 48, "dsv3": 32, "stress": 96}
+CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 1024, "phi": 256, "dsv3": 64, "stress": 1024}
 
 
 def main():

@@ -128,6 +128,7 @@ template <int W> struct Pack<float, W> {
 #pragma unroll
     for (int i = 0; i < W; i += 4) *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
   }
+  __device__ static __forceinline__ void store_nt(float* p, const float (&v)[W]) { store(p, v); }
   __device__ static __forceinline__ void load(const float* p, float (&v)[W]) {
 #pragma unroll
     for (int i = 0; i < W; i += 4) {
@@ -143,6 +144,21 @@ template <int W> struct Pack<bf16_t, W> {
     for (int i = 0; i < W / 2; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
     if (W == 4) *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
     else *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[W / 2 - 2], w[W / 2 - 1]);
+  }
+  // the same with a streaming hint: for outputs that nothing on the chip reads again soon
+  __device__ static __forceinline__ void store_nt(bf16_t* p, const float (&v)[W]) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    uint32_t w[W / 2];
+#pragma unroll
+    for (int i = 0; i < W / 2; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    if (W == 4) {
+      u32x2 t = {w[0], w[1]};
+      __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+    } else {
+      u32x4 t = {w[0], w[1], w[W / 2 - 2], w[W / 2 - 1]};
+      __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+    }
   }
   __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[W]) {
     uint32_t w[W / 2];
@@ -342,8 +358,8 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
     constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= m_valid || n >= n_valid) return;
     const int64_t off = (int64_t)slot * p.c_slot + (int64_t)(m0 + m) * p.N + n0 + n;
-    Pack<T, W>::store((T*)p.C[z] + off, v[0]);
-    if (NB == 2) Pack<T, W>::store((T*)p.C[1] + off, v[NB - 1]);
+    Pack<T, W>::store_nt((T*)p.C[z] + off, v[0]);
+    if (NB == 2) Pack<T, W>::store_nt((T*)p.C[1] + off, v[NB - 1]);
   };
 #ifdef MOE_TRACE
   const unsigned long long t_start = (unsigned long long)wall_clock64();
