@@ -202,22 +202,24 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   const int n_valid = min(BN, p.N - n0);
   const int a_row0 = p.a_rows_out ? t.row0_out : t.row0_in;
   const int nk = (p.K + BK - 1) / BK;
-  const int per_pair = p.n_segs * nk;
-  auto src = [&](int it) __attribute__((always_inline)) {
-    IterSrc<T, NB> s;
-    const int pair = it / per_pair, rem = it % per_pair;
-    const int seg = rem / nk, k0 = (rem % nk) * BK;
-    s.a = (const T*)p.A[pair] + seg * p.a_seg + (int64_t)a_row0 * p.lda + k0;
-    const int64_t boff = (int64_t)t.group * p.b_group + seg * p.b_seg + (B_KC ? (int64_t)n0 * p.ldb + k0 : (int64_t)k0 * p.ldb + n0);
+  // Where the tiles of this block start in each segment of the sum over K (segments: first all of
+  // pair 0, then all of pair 1), and how many bytes of valid data follow the tile origins.
+  constexpr int64_t es = sizeof(T);
+  const int64_t b_tile = (int64_t)t.group * p.b_group + (B_KC ? (int64_t)n0 * p.ldb : (int64_t)n0);
+  const int64_t a_tile = (int64_t)a_row0 * p.lda;
+  const int64_t a_end = ((int64_t)(rows - 1) * p.lda + p.K) * es;
+  const int64_t b_end = B_KC ? ((int64_t)(n_valid - 1) * p.ldb + p.K) * es : ((int64_t)(p.K - 1) * p.ldb + (p.N - n0)) * es;
+  auto segf = [&](int sg) __attribute__((always_inline)) {
+    SegSrc<T, NB> s;
+    const int pair = sg >= p.n_segs ? 1 : 0;  // at most two pairs
+    const int seg = sg - pair * p.n_segs;
+    s.a = (const T*)p.A[pair] + a_tile + seg * p.a_seg;
+    const int64_t boff = b_tile + seg * p.b_seg;
     s.b[0] = (const T*)p.B[pair] + boff;
     if (NB == 2) s.b[NB - 1] = (const T*)p.Bdual + boff;
-    s.k_left = p.K - k0;
-    const int64_t es = sizeof(T);
-    const int64_t ab = ((int64_t)(rows - 1) * p.lda + (p.K - k0)) * es;
-    const int64_t bb = B_KC ? ((int64_t)(n_valid - 1) * p.ldb + (p.K - k0)) * es
-                            : ((int64_t)(p.K - k0 - 1) * p.ldb + (p.N - n0)) * es;
-    s.a_bytes = clip_u32(ab);
-    s.b_bytes = clip_u32(bb);
+    s.k_len = p.K;
+    s.a_bytes = a_end;
+    s.b_bytes = b_end;
     return s;
   };
   const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
@@ -257,7 +259,7 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       Pack<T, W>::store((T*)p.out[1] + off, du);
     }
   };
-  Core::run(smem, p.n_pairs * per_pair, src, p.lda, p.ldb, rows, n_valid, epi);
+  Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
 }
 
 #ifdef MOE_TRACE
@@ -333,7 +335,10 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
   // {group, rows, first row, compact slot}; without records every group has n_rows rows and its own slot
   const int4 gi = p.ginfo ? p.ginfo[blockIdx.y] : make_int4((int)blockIdx.y, p.n_rows, 0, (int)blockIdx.y);
-  const int g = gi.x, K = gi.y, start = gi.z, slot = gi.w;
+  // the record is the same for the whole block: keep it in scalar registers, and with it every
+  // address computation of the K loop
+  const int g = __builtin_amdgcn_readfirstlane(gi.x), K = __builtin_amdgcn_readfirstlane(gi.y),
+            start = __builtin_amdgcn_readfirstlane(gi.z), slot = __builtin_amdgcn_readfirstlane(gi.w);
   if (K <= 0 || K < p.k_min || K > p.k_max) return;
   // single-product kernels serve the two products of a dual GEMM through blockIdx.z
   const int z = NB == 1 ? blockIdx.z : 0;
@@ -342,16 +347,15 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
   const int a_row0 = start + (p.a_per_group ? g * p.n_rows : 0);
   const int b_row0 = start + (p.b_per_group ? g * p.n_rows : 0);
-  auto src = [&](int it) __attribute__((always_inline)) {
-    IterSrc<T, NB> s;
-    const int k0 = it * BK;
-    s.a = (const T*)p.A + (int64_t)(a_row0 + k0) * p.lda + m0;
-    s.b[0] = (const T*)p.B[z] + (int64_t)(b_row0 + k0) * p.ldb + n0;
-    if (NB == 2) s.b[NB - 1] = (const T*)p.B[1] + (int64_t)(b_row0 + k0) * p.ldb + n0;
-    s.k_left = K - k0;
+  auto segf = [&](int) __attribute__((always_inline)) {  // one segment: the rows of the group
+    SegSrc<T, NB> s;
+    s.a = (const T*)p.A + (int64_t)a_row0 * p.lda + m0;
+    s.b[0] = (const T*)p.B[z] + (int64_t)b_row0 * p.ldb + n0;
+    if (NB == 2) s.b[NB - 1] = (const T*)p.B[1] + (int64_t)b_row0 * p.ldb + n0;
+    s.k_len = K;
     const int64_t es = sizeof(T);
-    s.a_bytes = clip_u32(((int64_t)(K - k0 - 1) * p.lda + (p.M - m0)) * es);
-    s.b_bytes = clip_u32(((int64_t)(K - k0 - 1) * p.ldb + (p.N - n0)) * es);
+    s.a_bytes = ((int64_t)(K - 1) * p.lda + (p.M - m0)) * es;
+    s.b_bytes = ((int64_t)(K - 1) * p.ldb + (p.N - n0)) * es;
     return s;
   };
   auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) {
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
 #ifdef MOE_TRACE
   const unsigned long long t_start = (unsigned long long)wall_clock64();
 #endif
-  Core::run(smem, (K + BK - 1) / BK, src, p.lda, p.ldb, m_valid, n_valid, epi);
+  Core::run(smem, 1, (K + BK - 1) / BK, segf, p.lda, p.ldb, m_valid, n_valid, epi);
 #ifdef MOE_TRACE
   trace_put(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16, t_start);
 #endif
@@ -387,7 +391,11 @@ template <> struct Cores<PATH_BF16_DMA> {
   static constexpr int BM = 256, BN = 256;
   // one block of 8 wavefronts (two per SIMD, so that one can issue MFMAs while the other waits for a
   // load slot or a barrier) computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each product)
-  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 4>;
+#ifndef TALL_DEPTH
+#define TALL_DEPTH 1
+#define TALL_BK 64
+#endif
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 4, TALL_DEPTH, TALL_BK>;
   // weight gradients of groups with few rows: 128 x 128 outputs per product, one tile slot
   template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, 0>;
 };
@@ -407,7 +415,7 @@ template <int NB, bool B_KC> struct RowCores<PATH_BF16_DMA, NB, B_KC> {
   // operand, the 64-row one 4.
   template <int KIND>
   using tile = MfmaDmaCore<(KIND == 0 ? 256 : KIND == 1 ? 128 : 64), 256 / NB, NB, true, B_KC, 2, 4,
-                           (KIND == 0 ? 1 : KIND == 1 ? 2 : 3)>;
+                           (KIND == 0 ? TALL_DEPTH : KIND == 1 ? 2 : 3), (KIND == 0 ? TALL_BK : 64)>;
 };
 
 static int pick_path(const moe_shape_t* s) {

@@ -4,24 +4,45 @@
 // Both cores compute, for one block, acc[nb][..] = sum over iterations of A_tile * B_tile(nb)
 // and hand groups of four consecutive columns to an epilogue functor:
 //     epi(m, n, vals)   m, n relative to the block tile;  vals[nb][0..3] = C[m][n..n+3]
-// A source iterator supplies, per K iteration, the base pointers and the valid extents.
+// The sum over K runs over n_segs segments of nk iterations each (segments: the shared experts of
+// a down projection, the two products of an input gradient); a segment functor supplies where the
+// tiles of a segment start, and the cores step along K from there themselves.
 #pragma once
 
 #include "moe_common.h"
 
 namespace moe {
 
-// What one K iteration reads.  Pointers are already offset to the tile's first row/column;
+// Start of one segment.  Pointers are already offset to the tile's first row/column at k = 0;
 // "kc" (K-contiguous) operands are [rows][K] row-major, otherwise [K][rows] row-major.
+template <typename T, int NB>
+struct SegSrc {
+  const T* a;        // A tile origin
+  const T* b[NB];    // B tile origin(s)
+  int k_len;         // values of K in the segment
+  // bytes from the origins to the end of the valid data of the tile (used by the cores that load
+  // through bounds-checked buffer descriptors: anything at or beyond reads as zero)
+  int64_t a_bytes, b_bytes;
+};
+
+// What one K iteration reads, for the cores that address element by element.
 template <typename T, int NB>
 struct IterSrc {
   const T* a;        // A tile origin for this iteration (k offset included)
   const T* b[NB];    // B tile origin(s)
   int k_left;        // valid K elements from this origin on
-  // bytes from the origin to the end of the valid data of this tile (used by the cores that load
-  // through bounds-checked buffer descriptors: anything at or beyond reads as zero)
-  uint32_t a_bytes, b_bytes;
 };
+template <typename T, int NB, bool A_KC, bool B_KC, class SegFn>
+__device__ __forceinline__ IterSrc<T, NB> iter_src(SegFn& segf, int it, int nk, int BK, int64_t lda, int64_t ldb) {
+  const int sg = it / nk, k0 = (it - sg * nk) * BK;
+  const SegSrc<T, NB> g = segf(sg);
+  IterSrc<T, NB> s;
+  s.a = g.a + (A_KC ? (int64_t)k0 : (int64_t)k0 * lda);
+#pragma unroll
+  for (int nb = 0; nb < NB; nb++) s.b[nb] = g.b[nb] + (B_KC ? (int64_t)k0 : (int64_t)k0 * ldb);
+  s.k_left = g.k_len - k0;
+  return s;
+}
 
 // ------------------------------------------------------------------------------ fp32 core
 template <int NB, bool A_KC, bool B_KC>
@@ -31,9 +52,11 @@ struct F32Core {
   static constexpr int LD = 64 + 4;
   static constexpr int LDS_BYTES = (BK * LD + NB * BK * LD) * 4;
 
-  template <class SrcFn, class Epi>
-  __device__ static void run(char* smem, int n_iters, SrcFn src, int64_t lda, int64_t ldb, int m_valid,
+  template <class SegFn, class Epi>
+  __device__ static void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb, int m_valid,
                              int n_valid, Epi epi) {
+    const int n_iters = n_segs * nk;
+    auto src = [&](int it) { return iter_src<float, NB, A_KC, B_KC>(segf, it, nk, BK, lda, ldb); };
     float* As = (float*)smem;            // [BK][LD]  (k major)
     float* Bs = As + BK * LD;            // [NB][BK][LD]
     const int tid = threadIdx.x;
@@ -204,9 +227,11 @@ struct MfmaCore {
           acc[nb][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb][j], f.a[i], acc[nb][i][j], 0, 0, 0);
   }
 
-  template <class SrcFn, class Epi>
-  __device__ static void run(char* smem, int n_iters, SrcFn src, int64_t lda, int64_t ldb, int m_valid,
+  template <class SegFn, class Epi>
+  __device__ static void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb, int m_valid,
                              int n_valid, Epi epi) {
+    const int n_iters = n_segs * nk;
+    auto src = [&](int it) { return iter_src<bf16_t, NB, A_KC, B_KC>(segf, it, nk, BK, lda, ldb); };
     bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
@@ -287,14 +312,17 @@ struct MfmaCore {
 // descriptor's num_records, which provides the zero fill of ragged row and K tails.
 // Requires K-contiguous operands to have K % 64 == 0 (a K tail inside a row cannot be masked).
 //
-// LDS layouts (bf16 elements), BK = 64, no padding:
-//  K-contiguous operand [rows][64]: 16-byte piece c of a row sits at position c ^ ((row/2)%8).
-//  row-contiguous operand [64 k][ROWS]: piece c (8 columns) of k-row k sits at position
+// LDS layouts (bf16 elements), no padding; a tile slot holds BK = 64 or 32 values of K:
+//  K-contiguous operand [rows][BK]: 16-byte piece c of a row sits at position c ^ ((row/2)%8)
+//    (BK = 64) or c ^ ((row/4)%4) (BK = 32): the 16 rows one phase of a 16-byte-per-lane read
+//    touches then cover all banks once.
+//  row-contiguous operand [BK k][ROWS]: piece c (8 columns) of k-row k sits at position
 //    c ^ (4*(k%4)), which spreads the four k rows of a transposing read over all banks.
-template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, int DEPTH = 1>
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, int DEPTH = 1, int BK_ = 64>
 struct MfmaDmaCore {
   typedef bf16_t T;
-  static constexpr int BM = BM_, BN = BN_, BK = 64;
+  static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  static constexpr int KS = BK / 16;  // MFMA k-steps per tile slot
   static constexpr int WM = WM_, WN = WN_;
   static constexpr int NW = WM * WN, NT = 64 * NW;  // wavefronts and threads per block
   static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -308,19 +336,25 @@ struct MfmaDmaCore {
   //     slots per operand and the loads of iteration t + DEPTH issued in iteration t, so that DEPTH
   //     whole K steps are in flight per CU; the latency of an HBM stream, not the matrix pipe, sets
   //     the pace there.
+  //  >= 2 with BK = 32  (tall tiles again): the same DEPTH + 1 slots, but half as wide, so that
+  //     LDS holds one tile being multiplied and DEPTH on their way in; hand-interleaved like 1.
   //  0  (weight gradients of groups with a handful of rows: K is one or two steps): one slot, no
   //     pipeline, small enough in LDS and registers for several blocks per CU, which is what hides
   //     latency when a block's life is one K iteration and an epilogue.
   static constexpr bool RING = DEPTH == 1;
+  static constexpr bool SPREAD = DEPTH >= 2 && BK == 32;
   static constexpr int A_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 3 : DEPTH + 1;
   static constexpr int B_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 2 : DEPTH + 1;
   static constexpr int B_SET_ELEMS = NB * B_ELEMS;
   static constexpr int TILE_BYTES = (A_SLOTS * A_ELEMS + B_SLOTS * B_SET_ELEMS) * 2;
   static constexpr int STAGING_BYTES = NW * NB * 32 * ((BN_ / WN_) + 4) * 4;  // epilogue, see run()
   static constexpr int LDS_BYTES = TILE_BYTES > STAGING_BYTES ? TILE_BYTES : STAGING_BYTES;
-  static constexpr int A_NI = BM / (8 * NW), B_NI = BN / (8 * NW);  // wave-wide loads per wave and tile
+  static constexpr int A_NI = BM * BK / (512 * NW), B_NI = BN * BK / (512 * NW);  // wave-wide loads per wave and tile
+  static constexpr int PR_KC = BK / 8;  // 16-byte pieces per row of a K-contiguous tile
+  static_assert(BK == 64 || BK == 32, "a tile slot holds 64 or 32 values of K");
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
-  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "every wave issues the same number of 1 KB loads per tile");
+  static_assert(BM * BK % (512 * NW) == 0 && BN * BK % (512 * NW) == 0,
+                "every wave issues the same number of 1 KB loads per tile");
   static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "wave tile must be a multiple of 32");
   static_assert((A_KC || BM % 128 == 0) && (B_KC || BN % 128 == 0),
                 "swizzle of row-contiguous tiles needs >= 16 pieces per k row");
@@ -329,14 +363,16 @@ struct MfmaDmaCore {
 
   // Byte offset (from the tile origin in memory) of the piece that lane `lane` of wave `wave`
   // fetches with its FIRST load.  The j-th load of the same lane is j * load_stride() rows further
-  // on (the swizzle terms do not depend on j), so one offset register per operand is enough; the
-  // j-dependent part moves into the descriptor base, which keeps it inside the bounds check.
+  // on (the swizzle terms do not depend on j); run() keeps one offset register per load, so that
+  // the K loop spends no instructions on addresses and the whole offset stays inside the
+  // descriptor's bounds check.
+  __device__ static __forceinline__ int kc_swizzle(int row) { return ((row * PR_KC) >> 4) & (PR_KC - 1); }
   template <int ROWS, bool KC>
   __device__ static __forceinline__ uint32_t piece_offset(int wave, int lane, uint32_t ld) {
     const int q = wave * 64 + lane;  // linear 16-byte piece of the LDS tile
     if (KC) {
-      const int row = q >> 3, pos = q & 7;
-      const int c = pos ^ ((row >> 1) & 7);
+      const int row = q / PR_KC, pos = q % PR_KC;
+      const int c = pos ^ kc_swizzle(row);
       return (uint32_t)row * ld * 2u + (uint32_t)c * 16u;
     } else {
       constexpr int PR = ROWS / 8;
@@ -348,31 +384,24 @@ struct MfmaDmaCore {
   // rows of the memory operand (K-contiguous: tile rows; row-contiguous: k rows) between two
   // consecutive loads of a wave: NW waves x 1 KB of LDS tile per round
   template <int ROWS, bool KC>
-  __device__ static constexpr int load_stride() { return KC ? 8 * NW : 512 * NW / ROWS; }
+  __device__ static constexpr int load_stride() { return KC ? 512 * NW / BK : 512 * NW / ROWS; }
 
   // One wave-wide 16-byte-per-lane load straight into LDS: the n-th 1 KB piece of this wave's share
   // of a tile.  Written as inline assembly so that the compiler does not serialise it against the
   // LDS reads of the other stage (it would wait for vmcnt(0) before every ds_read that may alias);
   // run() waits for the loads itself before its barrier.
   typedef __attribute__((ext_vector_type(4))) int rsrc_t;
-  template <int ROWS, bool KC>
-  __device__ static __forceinline__ void issue_one(const bf16_t* base, uint32_t bytes, uint32_t lds_tile_addr, int wave,
-                                                   uint32_t voff, uint32_t ld, int j) {
-    const uint32_t skip = (uint32_t)(j * load_stride<ROWS, KC>()) * ld * 2u;  // bytes before the j-th load
-    const uint64_t p = (uint64_t)base + skip;
-    // raw buffer descriptor: 48-bit base, stride 0, num_records in bytes, 32-bit data format
-    rsrc_t rsrc;
-    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
-    rsrc[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
-    rsrc[2] = __builtin_amdgcn_readfirstlane((int)(bytes > skip ? bytes - skip : 0u));
-    rsrc[3] = 0x00020000;
-    const uint32_t dst = lds_tile_addr + (uint32_t)(j * NW + wave) * 1024u;
-    // The compiler's hazard recogniser does not look inside inline assembly.  Two hazards of this
-    // hardware generation apply here: an SGPR written by a VALU instruction (v_readfirstlane, which
-    // the compiler uses to make descriptor words uniform) must not be read by a vector memory
-    // instruction within 5 wait states, and M0 must not be read by an LDS-DMA load in the wait
-    // state after its write.  The s_nop 4 covers both (the operands are set up before the statement).
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 4\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+  // `rsrc` is the raw buffer descriptor of the tile (48-bit base, stride 0, byte count, 32-bit data
+  // format), `voff` the lane's byte offset from its base (piece_offset plus the rows of the earlier
+  // loads of the tile), `dst` the LDS byte address of this wave's 1 KB piece.
+  //
+  // The compiler's hazard recogniser does not look inside inline assembly.  M0 must not be read by an
+  // LDS-DMA load in the wait state after its write, hence the s_nop.  The descriptor words must not
+  // have been written by a VALU instruction (v_readfirstlane and the like) in the five wait states
+  // before the load: they are kept in scalar registers and stepped with scalar instructions only
+  // (see Cursor), far from any vector instruction that could produce them.
+  __device__ static __forceinline__ void issue_one(const rsrc_t& rsrc, uint32_t dst, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :
                  : "s"(dst), "v"(voff), "s"(rsrc)
                  : "memory");
@@ -382,8 +411,8 @@ struct MfmaDmaCore {
   // All lane-dependent address arithmetic is done once (lane_offsets); inside the K loop a
   // fragment address is a per-lane base plus a compile-time constant, which the LDS instructions
   // carry in their offset field.
-  //   K-contiguous tile:   off[ks] for the wave's first 32 rows; 32 more rows = +32*64 elements
-  //                        (the swizzle (row/2)%8 repeats every 16 rows)
+  //   K-contiguous tile:   off[ks] for the wave's first 32 rows; 32 more rows = +32*BK elements
+  //                        (the swizzle repeats every 16 rows)
   //   row-contiguous tile: off[t] for the t-th group of 32 columns at k-step 0;
   //                        k-step ks = +16*ks*ROWS elements, second half of the 8 k = +4*ROWS
   template <int ROWS, bool KC, int NTILE>
@@ -391,7 +420,7 @@ struct MfmaDmaCore {
     if (KC) {
       const int row = w0 + (lane & 31);
 #pragma unroll
-      for (int ks = 0; ks < 4; ks++) off[ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 1) & 7)) << 3);
+      for (int ks = 0; ks < KS; ks++) off[ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ kc_swizzle(row)) << 3);
     } else {
       // transposing read: within 16 lanes, lane s points at 4 consecutive columns of k-row
       // kb + s/4, starting at column 4*(s%4); it receives k = kb..kb+3 of column s.
@@ -446,9 +475,88 @@ struct MfmaDmaCore {
                  : "memory");
   }
 
-  template <class SrcFn, class Epi>
-  __device__ static __forceinline__ void run(char* smem, int n_iters, SrcFn src, int64_t lda, int64_t ldb,
+  // Position of a stream of tile loads along K.  The K loop pays for every scalar instruction between
+  // its MFMAs, so stepping is a handful of additions; the segment functor is consulted only where a
+  // segment starts.  Once the product is exhausted the steps are zero and the byte counts stay at
+  // zero: loads issued from there on read nothing and deliver zeros.
+  struct Cursor {
+    rsrc_t ad, bd[NB];      // buffer descriptors of the A tile and the B tile(s) at this position
+    int64_t a_rem, b_rem;   // bytes from the tile origins to the end of the tile's valid data
+    int64_t a_step, b_step; // bytes by which one iteration moves the origins
+    int k_left, k_step;     // valid values of K from the origins on
+    int ki, sg;
+  };
+  // byte count of a descriptor: 32 bits, saturating (built from the halves: scalar instructions only)
+  __device__ static __forceinline__ int clip_rem(int64_t v) {
+    const int32_t hi = (int32_t)(v >> 32);
+    return hi < 0 ? 0 : hi > 0 ? -1 : (int)(uint32_t)v;
+  }
+  __device__ static __forceinline__ rsrc_t make_desc(const bf16_t* base, int64_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    rsrc_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(p >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane(clip_rem(bytes));
+    r[3] = 0x00020000;
+    return r;
+  }
+  // moves a descriptor's base by `step` bytes (the base stays below 2^48) and sets its byte count
+  __device__ static __forceinline__ void move_desc(rsrc_t& r, int64_t step, int64_t bytes) {
+    const uint64_t p = (((uint64_t)(uint32_t)r[1] << 32) | (uint32_t)r[0]) + (uint64_t)step;
+    r[0] = (int)(uint32_t)p;
+    r[1] = (int)(uint32_t)(p >> 32);
+    r[2] = clip_rem(bytes);
+  }
+  template <class SegFn>
+  __device__ static __forceinline__ void seek(Cursor& c, SegFn& segf, int sg, int n_segs, int nk, int64_t lda,
+                                              int64_t ldb) {
+    c.ki = 0;
+    c.sg = sg;
+    if (sg < n_segs && nk > 0) {
+      const SegSrc<bf16_t, NB> g = segf(sg);
+      c.a_rem = g.a_bytes;
+      c.b_rem = g.b_bytes;
+      c.ad = make_desc(g.a, c.a_rem);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) c.bd[nb] = make_desc(g.b[nb], c.b_rem);
+      c.a_step = A_KC ? (int64_t)BK * 2 : (int64_t)BK * 2 * lda;
+      c.b_step = B_KC ? (int64_t)BK * 2 : (int64_t)BK * 2 * ldb;
+      c.k_left = g.k_len;
+      c.k_step = BK;
+    } else {
+      // exhausted (or nothing to do): zero-length descriptors that stay where they are
+      c.a_rem = c.b_rem = c.a_step = c.b_step = 0;
+      c.k_left = c.k_step = 0;
+      if (sg == 0) {
+        c.ad = make_desc(nullptr, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) c.bd[nb] = make_desc(nullptr, 0);
+      } else {
+        c.ad[2] = 0;
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) c.bd[nb][2] = 0;
+      }
+    }
+  }
+  template <class SegFn>
+  __device__ static __forceinline__ void next(Cursor& c, SegFn& segf, int n_segs, int nk, int64_t lda, int64_t ldb) {
+    c.ki++;
+    if (c.ki != nk) {
+      c.a_rem -= c.a_step;
+      c.b_rem -= c.b_step;
+      move_desc(c.ad, c.a_step, c.a_rem);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) move_desc(c.bd[nb], c.b_step, c.b_rem);
+      c.k_left -= c.k_step;
+    } else {
+      seek(c, segf, c.sg + 1, n_segs, nk, lda, ldb);
+    }
+  }
+
+  template <class SegFn, class Epi>
+  __device__ static __forceinline__ void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb,
                                              int m_valid, int n_valid, Epi epi) {
+    const int n_iters = n_segs * nk;
     bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -474,26 +582,29 @@ struct MfmaDmaCore {
         for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
     asm volatile("s_nop 7" ::: "memory");
 
-    const uint32_t voa = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda);
-    const uint32_t vob = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb);
+    // per-lane byte offsets of this wave's loads of a tile, fixed for the whole K loop
+    uint32_t voa[A_NI], vob[B_NI];
+#pragma unroll
+    for (int j = 0; j < A_NI; j++)
+      voa[j] = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda) + (uint32_t)(j * load_stride<BM, A_KC>()) * (uint32_t)lda * 2u;
+#pragma unroll
+    for (int j = 0; j < B_NI; j++)
+      vob[j] = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb) + (uint32_t)(j * load_stride<BN, B_KC>()) * (uint32_t)ldb * 2u;
+    // LDS byte addresses: this wave's first piece of A slot 0 and of B slot 0
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
-    // LDS byte addresses of the tile slots
-    const uint32_t lds_b0 = lds_addr + (uint32_t)(A_SLOTS * A_ELEMS * 2);
-    auto load_a = [&](const IterSrc<bf16_t, NB>& s, int slot, int j) __attribute__((always_inline)) {
-      issue_one<BM, A_KC>(s.a, s.a_bytes, lds_addr + (uint32_t)(slot * A_ELEMS * 2), wave, voa, (uint32_t)lda, j);
+    const uint32_t lds_a0 = lds_addr + (uint32_t)wave * 1024u;
+    const uint32_t lds_b0 = lds_a0 + (uint32_t)(A_SLOTS * A_ELEMS * 2);
+    auto load_a = [&](const Cursor& c, int slot, int j) __attribute__((always_inline)) {
+      issue_one(c.ad, lds_a0 + (uint32_t)(slot * A_ELEMS * 2) + (uint32_t)(j * NW) * 1024u, voa[j]);
     };
-    auto load_b = [&](const IterSrc<bf16_t, NB>& s, int slot, int n) __attribute__((always_inline)) {
+    auto load_b = [&](const Cursor& c, int slot, int n) __attribute__((always_inline)) {
       const int nb = n / B_NI, j = n % B_NI;
-      issue_one<BN, B_KC>(s.b[nb], s.b_bytes, lds_b0 + (uint32_t)((slot * B_SET_ELEMS + nb * B_ELEMS) * 2), wave, vob,
-                          (uint32_t)ldb, j);
+      issue_one(c.bd[nb], lds_b0 + (uint32_t)((slot * B_SET_ELEMS + nb * B_ELEMS) * 2) + (uint32_t)(j * NW) * 1024u, vob[j]);
     };
-    // a source with zero-length descriptors: the loads still issue (the wait counts below stay
-    // constant and the K loop free of branches) but read nothing and deliver zeros
-    auto source = [&](int it) __attribute__((always_inline)) {
-      IterSrc<bf16_t, NB> s = src(it < n_iters ? it : n_iters - 1);
-      if (it >= n_iters) s.a_bytes = s.b_bytes = 0;
-      return s;
-    };
+    // Loads beyond the last iteration still issue (the wait counts below stay constant and the K
+    // loop free of branches): an exhausted cursor makes them read nothing.
+    auto start = [&](Cursor& c) __attribute__((always_inline)) { seek(c, segf, 0, n_segs, nk, lda, ldb); };
+    auto step = [&](Cursor& c) __attribute__((always_inline)) { next(c, segf, n_segs, nk, lda, ldb); };
 
     static_assert(TM <= 4 && TN <= 4, "lane_offsets holds four tiles per operand");
     int ao[4], bo[4];
@@ -501,17 +612,89 @@ struct MfmaDmaCore {
     lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
 
     constexpr int kLoadsB = NB * B_NI;  // loads per wave for the B tiles of one iteration
-    if constexpr (DEPTH >= 2) {
+    if constexpr (SPREAD) {
+      // Deep ring of narrow slots: DEPTH tiles (of BK values of K each) are in flight while one is
+      // multiplied, so nearly all of LDS holds data on its way in, which is what a stream with a
+      // share of L2 misses needs.  The instruction stream is interleaved by hand as in the ring of
+      // three below: per MFMA at most one fragment read and one tile load, the barrier half-way
+      // through the last k-step with MFMAs already queued behind it.
+      constexpr int L = A_NI + kLoadsB;  // loads per wave and iteration
+      constexpr int NS = DEPTH + 1;
+      constexpr int kHalf = kMfma / 2, kLate = kMfma - kHalf;
+      constexpr int kSlots = (KS - 1) * kMfma + kHalf;
+      static_assert((DEPTH - 1) * L <= 63, "the wait count of the oldest tile must be encodable");
+      static_assert(KS % 2 == 0, "fragment buffers alternate per k-step and restart at 0 per tile");
+      auto load_n = [&](const Cursor& s0, int slot, int n) __attribute__((always_inline)) {
+        if (n < A_NI) load_a(s0, slot, n);
+        else load_b(s0, slot, n - A_NI);
+      };
+      Cursor sn;  // tile it + DEPTH
+      start(sn);
+      if (n_iters > 0) {
+        for (int it = 0; it < DEPTH; it++) {
+#pragma unroll
+          for (int n = 0; n < L; n++) load_n(sn, it, n);
+          step(sn);
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * L) : "memory");
+      __syncthreads();
+      Frags f[2];
+#pragma unroll
+      for (int r = 0; r < kFragLoads; r++) load_frag_n(lds, lds + A_SLOTS * A_ELEMS, ao, bo, 0, r, f[0]);
+      int cur = 0;  // slot of this iteration's tile
+      for (int it = 0; it < n_iters; it++) {
+        const int nxt = cur == NS - 1 ? 0 : cur + 1;
+        const int fill = cur == 0 ? NS - 1 : cur - 1;  // read in the previous iteration, free since its barrier
+        const bf16_t* As = lds + cur * A_ELEMS;
+        const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + cur * B_SET_ELEMS;
+        const bf16_t* An = lds + nxt * A_ELEMS;
+        const bf16_t* Bn = lds + A_SLOTS * A_ELEMS + nxt * B_SET_ELEMS;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+#pragma unroll
+          for (int m = 0; m < kMfma; m++) {
+            if (ks < KS - 1) {
+#pragma unroll
+              for (int r = m * kFragLoads / kMfma; r < (m + 1) * kFragLoads / kMfma; r++)
+                load_frag_n(As, Bs, ao, bo, ks + 1, r, f[(ks + 1) & 1]);
+            } else {
+              if (m == kHalf) {
+                // tile it+1 has landed once only the DEPTH - 1 younger tiles are outstanding; every
+                // wave is past its last read of this iteration's tile
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * L) : "memory");
+                __syncthreads();
+              }
+              if (m >= kHalf) {
+#pragma unroll
+                for (int r = (m - kHalf) * kFragLoads / kLate; r < (m - kHalf + 1) * kFragLoads / kLate; r++)
+                  load_frag_n(An, Bn, ao, bo, 0, r, f[0]);
+              }
+            }
+            const int slot = ks * kMfma + m;
+            if (slot < kSlots) {
+#pragma unroll
+              for (int n = slot * L / kSlots; n < (slot + 1) * L / kSlots; n++) load_n(sn, fill, n);
+            }
+            mfma_n(acc, f[ks & 1], m);
+          }
+        }
+        step(sn);
+        cur = nxt;
+      }
+    } else if constexpr (DEPTH >= 2) {
       // streaming pipeline: tiles t .. t+DEPTH-1 in flight while tile t is multiplied
       constexpr int L = A_NI + kLoadsB;  // loads per wave and iteration
       static_assert((DEPTH - 1) * L <= 63, "the wait count of the oldest tile must be encodable");
+      Cursor s0;  // the next tile to request
+      start(s0);
       auto issue_tile = [&](int it) __attribute__((always_inline)) {
-        const IterSrc<bf16_t, NB> s0 = source(it);
         const int slot = it % (DEPTH + 1);
 #pragma unroll
         for (int j = 0; j < A_NI; j++) load_a(s0, slot, j);
 #pragma unroll
         for (int n = 0; n < kLoadsB; n++) load_b(s0, slot, n);
+        step(s0);
       };
       if (n_iters > 0) {
         for (int it = 0; it < DEPTH; it++) issue_tile(it);
@@ -527,7 +710,7 @@ struct MfmaDmaCore {
         const bf16_t* As = lds + slot * A_ELEMS;
         const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + slot * B_SET_ELEMS;
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
+        for (int ks = 0; ks < KS; ks++) {
           Frags f;
 #pragma unroll
           for (int r = 0; r < kFragLoads; r++) load_frag_n(As, Bs, ao, bo, ks, r, f);
@@ -537,8 +720,9 @@ struct MfmaDmaCore {
       }
     } else if constexpr (!RING) {
       // single slot: load a tile, wait, multiply; k-steps beyond the rows of K are skipped
+      Cursor s0;
+      start(s0);
       for (int it = 0; it < n_iters; it++) {
-        const IterSrc<bf16_t, NB> s0 = source(it);
         if (it > 0) __syncthreads();
 #pragma unroll
         for (int j = 0; j < A_NI; j++) load_a(s0, 0, j);
@@ -547,7 +731,7 @@ struct MfmaDmaCore {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < 4; ks++) {
+        for (int ks = 0; ks < KS; ks++) {
           if (ks * 16 >= s0.k_left) continue;  // uniform: the remaining k rows of the tile are zero
           Frags f;
 #pragma unroll
@@ -555,16 +739,22 @@ struct MfmaDmaCore {
 #pragma unroll
           for (int m = 0; m < kMfma; m++) mfma_n(acc, f, m);
         }
+        step(s0);
       }
     } else {
+    Cursor s1, s2;  // s1: the B tiles of iteration it + 1; s2: the A tile of iteration it + 2
+    start(s1);
+    start(s2);
     if (n_iters > 0) {
-      IterSrc<bf16_t, NB> s0 = source(0), s1 = source(1);
 #pragma unroll
-      for (int j = 0; j < A_NI; j++) load_a(s0, 0, j);
+      for (int j = 0; j < A_NI; j++) load_a(s2, 0, j);
 #pragma unroll
-      for (int n = 0; n < kLoadsB; n++) load_b(s0, 0, n);
+      for (int n = 0; n < kLoadsB; n++) load_b(s1, 0, n);
+      step(s1);
+      step(s2);
 #pragma unroll
-      for (int j = 0; j < A_NI; j++) load_a(s1, 1, j);
+      for (int j = 0; j < A_NI; j++) load_a(s2, 1, j);
+      step(s2);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -580,7 +770,7 @@ struct MfmaDmaCore {
     //     read the first fragments of iteration t+1 under the remaining MFMAs.
     constexpr int kLoads = kLoadsB + A_NI;
     constexpr int kHalf = kMfma / 2;                 // MFMAs of the last k-step before the barrier
-    constexpr int kSlots = 3 * kMfma + kHalf;        // MFMA slots before the barrier: all loads issue here
+    constexpr int kSlots = (KS - 1) * kMfma + kHalf; // MFMA slots before the barrier: all loads issue here
     constexpr int kLate = kMfma - kHalf;             // MFMAs after the barrier
     Frags f[2];
 #pragma unroll
@@ -594,12 +784,11 @@ struct MfmaDmaCore {
       const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + b_cur * B_SET_ELEMS;
       const bf16_t* An = lds + a_nxt * A_ELEMS;
       const bf16_t* Bn = lds + A_SLOTS * A_ELEMS + b_nxt * B_SET_ELEMS;
-      const IterSrc<bf16_t, NB> s1 = source(it + 1), s2 = source(it + 2);
 #pragma unroll
-      for (int ks = 0; ks < 4; ks++) {
+      for (int ks = 0; ks < KS; ks++) {
 #pragma unroll
         for (int m = 0; m < kMfma; m++) {
-          if (ks < 3) {
+          if (ks < KS - 1) {
             // fragment loads of k-step ks+1, spread over the MFMAs of ks
 #pragma unroll
             for (int r = m * kFragLoads / kMfma; r < (m + 1) * kFragLoads / kMfma; r++)
@@ -630,6 +819,8 @@ struct MfmaDmaCore {
           mfma_n(acc, f[ks & 1], m);
         }
       }
+      step(s1);
+      step(s2);
       a_cur = a_nxt;
       b_cur = b_nxt;
     }
