@@ -389,13 +389,10 @@ template <> struct Cores<PATH_BF16> {
 };
 template <> struct Cores<PATH_BF16_DMA> {
   static constexpr int BM = 256, BN = 256;
-  // one block of 8 wavefronts (two per SIMD, so that one can issue MFMAs while the other waits for a
-  // load slot or a barrier) computes 256 x 256 outputs (dual GEMMs: 256 x 128 of each product)
-#ifndef TALL_DEPTH
-#define TALL_DEPTH 1
-#define TALL_BK 64
-#endif
-  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 4, TALL_DEPTH, TALL_BK>;
+  // one block of 4 wavefronts (one per SIMD, each with a 128 x 128 share: the fewest LDS reads and
+  // scalar instructions per MFMA, which is what the K loop is short of) computes 256 x 256 outputs
+  // (dual GEMMs: 256 x 128 of each product)
+  template <int NB, bool A_KC, bool B_KC> using core = MfmaDmaCore<256, 256 / NB, NB, A_KC, B_KC, 2, 2>;
   // weight gradients of groups with few rows: 128 x 128 outputs per product, one tile slot
   template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, 0>;
 };
@@ -409,13 +406,12 @@ template <int PATH, int NB, bool B_KC> struct RowCores {
 };
 template <int NB, bool B_KC> struct RowCores<PATH_BF16_DMA, NB, B_KC> {
   static constexpr int kKinds = 4;
-  // tile kinds 0..3 are cut for 256, 128, 64 and 32 rows; the last two share the 64-row core (eight
-  // wavefronts cannot split fewer rows and columns, and those tiles are bound by streaming the
-  // weights, not by MFMA work).  Pipeline depth by height: the 128-row tile fits 3 slots per
-  // operand, the 64-row one 4.
+  // tile kinds 0..3 are cut for 256, 128, 64 and 32 rows; the last two share the 64-row core (those
+  // tiles are bound by streaming the weights, not by MFMA work).  Pipeline depth by height: the
+  // 128-row tile fits 3 slots per operand, the 64-row one 4.
   template <int KIND>
-  using tile = MfmaDmaCore<(KIND == 0 ? 256 : KIND == 1 ? 128 : 64), 256 / NB, NB, true, B_KC, 2, 4,
-                           (KIND == 0 ? TALL_DEPTH : KIND == 1 ? 2 : 3), (KIND == 0 ? TALL_BK : 64)>;
+  using tile = MfmaDmaCore<(KIND == 0 ? 256 : KIND == 1 ? 128 : 64), 256 / NB, NB, true, B_KC, 2, 2,
+                           (KIND == 0 ? 1 : KIND == 1 ? 2 : 3)>;
 };
 
 static int pick_path(const moe_shape_t* s) {

@@ -312,16 +312,15 @@ struct MfmaCore {
 // descriptor's num_records, which provides the zero fill of ragged row and K tails.
 // Requires K-contiguous operands to have K % 64 == 0 (a K tail inside a row cannot be masked).
 //
-// LDS layouts (bf16 elements), no padding; a tile slot holds BK = 64 or 32 values of K:
-//  K-contiguous operand [rows][BK]: 16-byte piece c of a row sits at position c ^ ((row/2)%8)
-//    (BK = 64) or c ^ ((row/4)%4) (BK = 32): the 16 rows one phase of a 16-byte-per-lane read
-//    touches then cover all banks once.
-//  row-contiguous operand [BK k][ROWS]: piece c (8 columns) of k-row k sits at position
+// LDS layouts (bf16 elements), BK = 64, no padding:
+//  K-contiguous operand [rows][64]: 16-byte piece c of a row sits at position c ^ ((row/2)%8), so
+//    that the 16 rows one phase of a 16-byte-per-lane read touches cover all banks once.
+//  row-contiguous operand [64 k][ROWS]: piece c (8 columns) of k-row k sits at position
 //    c ^ (4*(k%4)), which spreads the four k rows of a transposing read over all banks.
-template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, int DEPTH = 1, int BK_ = 64>
+template <int BM_, int BN_, int NB, bool A_KC, bool B_KC, int WM_ = 2, int WN_ = 2, int DEPTH = 1>
 struct MfmaDmaCore {
   typedef bf16_t T;
-  static constexpr int BM = BM_, BN = BN_, BK = BK_;
+  static constexpr int BM = BM_, BN = BN_, BK = 64;
   static constexpr int KS = BK / 16;  // MFMA k-steps per tile slot
   static constexpr int WM = WM_, WN = WN_;
   static constexpr int NW = WM * WN, NT = 64 * NW;  // wavefronts and threads per block
@@ -336,13 +335,10 @@ struct MfmaDmaCore {
   //     slots per operand and the loads of iteration t + DEPTH issued in iteration t, so that DEPTH
   //     whole K steps are in flight per CU; the latency of an HBM stream, not the matrix pipe, sets
   //     the pace there.
-  //  >= 2 with BK = 32  (tall tiles again): the same DEPTH + 1 slots, but half as wide, so that
-  //     LDS holds one tile being multiplied and DEPTH on their way in; hand-interleaved like 1.
   //  0  (weight gradients of groups with a handful of rows: K is one or two steps): one slot, no
   //     pipeline, small enough in LDS and registers for several blocks per CU, which is what hides
   //     latency when a block's life is one K iteration and an epilogue.
   static constexpr bool RING = DEPTH == 1;
-  static constexpr bool SPREAD = DEPTH >= 2 && BK == 32;
   static constexpr int A_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 3 : DEPTH + 1;
   static constexpr int B_SLOTS = DEPTH == 0 ? 1 : DEPTH == 1 ? 2 : DEPTH + 1;
   static constexpr int B_SET_ELEMS = NB * B_ELEMS;
@@ -351,7 +347,6 @@ struct MfmaDmaCore {
   static constexpr int LDS_BYTES = TILE_BYTES > STAGING_BYTES ? TILE_BYTES : STAGING_BYTES;
   static constexpr int A_NI = BM * BK / (512 * NW), B_NI = BN * BK / (512 * NW);  // wave-wide loads per wave and tile
   static constexpr int PR_KC = BK / 8;  // 16-byte pieces per row of a K-contiguous tile
-  static_assert(BK == 64 || BK == 32, "a tile slot holds 64 or 32 values of K");
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts per block");
   static_assert(BM * BK % (512 * NW) == 0 && BN * BK % (512 * NW) == 0,
                 "every wave issues the same number of 1 KB loads per tile");
@@ -612,77 +607,7 @@ struct MfmaDmaCore {
     lane_offsets<BN, B_KC, TN>(wn0, lane, bo);
 
     constexpr int kLoadsB = NB * B_NI;  // loads per wave for the B tiles of one iteration
-    if constexpr (SPREAD) {
-      // Deep ring of narrow slots: DEPTH tiles (of BK values of K each) are in flight while one is
-      // multiplied, so nearly all of LDS holds data on its way in, which is what a stream with a
-      // share of L2 misses needs.  The instruction stream is interleaved by hand as in the ring of
-      // three below: per MFMA at most one fragment read and one tile load, the barrier half-way
-      // through the last k-step with MFMAs already queued behind it.
-      constexpr int L = A_NI + kLoadsB;  // loads per wave and iteration
-      constexpr int NS = DEPTH + 1;
-      constexpr int kHalf = kMfma / 2, kLate = kMfma - kHalf;
-      constexpr int kSlots = (KS - 1) * kMfma + kHalf;
-      static_assert((DEPTH - 1) * L <= 63, "the wait count of the oldest tile must be encodable");
-      static_assert(KS % 2 == 0, "fragment buffers alternate per k-step and restart at 0 per tile");
-      auto load_n = [&](const Cursor& s0, int slot, int n) __attribute__((always_inline)) {
-        if (n < A_NI) load_a(s0, slot, n);
-        else load_b(s0, slot, n - A_NI);
-      };
-      Cursor sn;  // tile it + DEPTH
-      start(sn);
-      if (n_iters > 0) {
-        for (int it = 0; it < DEPTH; it++) {
-#pragma unroll
-          for (int n = 0; n < L; n++) load_n(sn, it, n);
-          step(sn);
-        }
-      }
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * L) : "memory");
-      __syncthreads();
-      Frags f[2];
-#pragma unroll
-      for (int r = 0; r < kFragLoads; r++) load_frag_n(lds, lds + A_SLOTS * A_ELEMS, ao, bo, 0, r, f[0]);
-      int cur = 0;  // slot of this iteration's tile
-      for (int it = 0; it < n_iters; it++) {
-        const int nxt = cur == NS - 1 ? 0 : cur + 1;
-        const int fill = cur == 0 ? NS - 1 : cur - 1;  // read in the previous iteration, free since its barrier
-        const bf16_t* As = lds + cur * A_ELEMS;
-        const bf16_t* Bs = lds + A_SLOTS * A_ELEMS + cur * B_SET_ELEMS;
-        const bf16_t* An = lds + nxt * A_ELEMS;
-        const bf16_t* Bn = lds + A_SLOTS * A_ELEMS + nxt * B_SET_ELEMS;
-#pragma unroll
-        for (int ks = 0; ks < KS; ks++) {
-#pragma unroll
-          for (int m = 0; m < kMfma; m++) {
-            if (ks < KS - 1) {
-#pragma unroll
-              for (int r = m * kFragLoads / kMfma; r < (m + 1) * kFragLoads / kMfma; r++)
-                load_frag_n(As, Bs, ao, bo, ks + 1, r, f[(ks + 1) & 1]);
-            } else {
-              if (m == kHalf) {
-                // tile it+1 has landed once only the DEPTH - 1 younger tiles are outstanding; every
-                // wave is past its last read of this iteration's tile
-                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * L) : "memory");
-                __syncthreads();
-              }
-              if (m >= kHalf) {
-#pragma unroll
-                for (int r = (m - kHalf) * kFragLoads / kLate; r < (m - kHalf + 1) * kFragLoads / kLate; r++)
-                  load_frag_n(An, Bn, ao, bo, 0, r, f[0]);
-              }
-            }
-            const int slot = ks * kMfma + m;
-            if (slot < kSlots) {
-#pragma unroll
-              for (int n = slot * L / kSlots; n < (slot + 1) * L / kSlots; n++) load_n(sn, fill, n);
-            }
-            mfma_n(acc, f[ks & 1], m);
-          }
-        }
-        step(sn);
-        cur = nxt;
-      }
-    } else if constexpr (DEPTH >= 2) {
+    if constexpr (DEPTH >= 2) {
       // streaming pipeline: tiles t .. t+DEPTH-1 in flight while tile t is multiplied
       constexpr int L = A_NI + kLoadsB;  // loads per wave and iteration
       static_assert((DEPTH - 1) * L <= 63, "the wait count of the oldest tile must be encodable");
@@ -761,7 +686,7 @@ struct MfmaDmaCore {
 
     // A wave issues in order and a tile load holds it for as long as the memory pipeline has no
     // free slot, so the overlap of loads, LDS reads and MFMAs is written into the instruction
-    // stream itself (the second wave of the SIMD fills what is left).  Per K iteration t (4 k-steps
+    // stream itself.  Per K iteration t (4 k-steps
     // of kMfma MFMAs):
     //   - the fragments of k-step ks+1 are read from LDS during the MFMAs of ks, one per MFMA;
     //   - the loads of B(t+1), then of A(t+2), are spread evenly between the MFMAs;
