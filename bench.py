@@ -37,8 +37,8 @@ SYMBOL = {
     "gemm_fwd_down": "moe::row_gemm_kernel<moe::RowCores<2, 1, false>, 1, 0, false>(moe::RowGemm)",
     "gemm_bwd_dh": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 2, true>(moe::RowGemm)",
     "gemm_bwd_dx": "moe::row_gemm_kernel<moe::RowCores<2, 1, true>, 1, 0, true>(moe::RowGemm)",
-    "gemm_bwd_dwd": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 256, 1, false, false, 2, 4, 1>, 1>(moe::WGemm)",
-    "gemm_bwd_dwgu": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 128, 2, false, false, 2, 4, 1>, 2>(moe::WGemm)",
+    "gemm_bwd_dwd": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 256, 1, false, false, 2, 2, 1>, 1>(moe::WGemm)",
+    "gemm_bwd_dwgu": "moe::w_gemm_kernel<moe::MfmaDmaCore<256, 128, 2, false, false, 2, 2, 1>, 2>(moe::WGemm)",
     "gemm_bwd_dw_light": "moe::w_gemm_kernel<moe::MfmaDmaCore<128, 128, 1, false, false, 2, 2, 0>, 1>(moe::WGemm)",
 }
 

@@ -290,7 +290,23 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
   extern __shared__ __align__(16) char smem[];
   typedef typename CoreSet::template tile<0> Core0;
   const int ntn = (p.N + Core0::BN - 1) / Core0::BN;
-  const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  int mt, nt;
+  if (CoreSet::kKinds == 4) {
+    // Blocks go to the XCDs round-robin (block b runs on XCD b % 8) and the 32 CUs of an XCD share
+    // one L2, so the 32 blocks an XCD holds at a time should read as few different operand tiles as
+    // possible.  Tiles are numbered band by band (a band: kBandRows consecutive row tiles), column
+    // by column within a band, and each XCD takes runs of 32 consecutive tiles: 4 row tiles x 8
+    // column tiles, 12 operand streams for 32 tiles.
+    const int per_band = kBandRows * ntn;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int q = ((j >> 5) * 8 + xcd) * 32 + (j & 31);
+    const int band = q / per_band, r = q - band * per_band;
+    mt = band * kBandRows + r % kBandRows;
+    nt = r / kBandRows;
+  } else {
+    mt = blockIdx.x / ntn;
+    nt = blockIdx.x % ntn;
+  }
   RowTile t;
   if (p.tiles) {
     if (mt >= *p.n_tiles) return;
@@ -333,8 +349,10 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   typedef typename Core::T T;
   extern __shared__ __align__(16) char smem[];
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
+  const int ntn = (p.N + BN - 1) / BN;
+  const int rank = blockIdx.y, mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
   // {group, rows, first row, compact slot}; without records every group has n_rows rows and its own slot
-  const int4 gi = p.ginfo ? p.ginfo[blockIdx.y] : make_int4((int)blockIdx.y, p.n_rows, 0, (int)blockIdx.y);
+  const int4 gi = p.ginfo ? p.ginfo[rank] : make_int4(rank, p.n_rows, 0, rank);
   // the record is the same for the whole block: keep it in scalar registers, and with it every
   // address computation of the K loop
   const int g = __builtin_amdgcn_readfirstlane(gi.x), K = __builtin_amdgcn_readfirstlane(gi.y),
@@ -342,8 +360,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   if (K <= 0 || K < p.k_min || K > p.k_max) return;
   // single-product kernels serve the two products of a dual GEMM through blockIdx.z
   const int z = NB == 1 ? blockIdx.z : 0;
-  const int ntn = (p.N + BN - 1) / BN;
-  const int m0 = (blockIdx.x / ntn) * BM, n0 = (blockIdx.x % ntn) * BN;
+  const int m0 = mt * BM, n0 = nt * BN;
   const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
   const int a_row0 = start + (p.a_per_group ? g * p.n_rows : 0);
   const int b_row0 = start + (p.b_per_group ? g * p.n_rows : 0);
@@ -442,7 +459,10 @@ static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipSt
     attr_done = true;
   }
   ProfScope prof(label, st);
-  hipLaunchKernelGGL(kern, dim3((unsigned)(n_mt * ntn)), dim3(Core::NT), Core::LDS_BYTES, st, p);
+  // LDS-DMA path: whole bands of kBandRows row tiles, handed out in runs of 32 tiles to 8 XCDs
+  const unsigned n_blocks = CoreSet::kKinds == 4 ? (unsigned)ceil_div(ceil_div(n_mt, kBandRows) * kBandRows * ntn, 256) * 256u
+                                                 : (unsigned)(n_mt * ntn);
+  hipLaunchKernelGGL(kern, dim3(n_blocks), dim3(Core::NT), Core::LDS_BYTES, st, p);
 }
 
 template <class Core, int NB>

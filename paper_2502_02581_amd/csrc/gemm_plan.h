@@ -17,6 +17,8 @@ __host__ __device__ inline int tile_rows(const RowTile& t) { return t.rows & 0xf
 __host__ __device__ inline int tile_kind(const RowTile& t) { return (t.rows >> 16) & 3; }
 // heights of the tile kinds of the mixed-height plan (kind 0 is the full tile)
 __host__ __device__ inline int kind_height(int kind) { return 256 >> kind; }
+// row tiles per band of the XCD-aware tile order of the LDS-DMA path
+constexpr int kBandRows = 4;
 
 // Device-built plan, laid out in the workspace.
 struct Plan {
