@@ -23,6 +23,9 @@ open are taken as follows (each is a choice of this build, not of the paper):
     (Eq. 2: experts summed along d_ff).
   * the gating network that produces the logits (router_fwd / router_bwd) is one
     linear map without bias; the paper only calls it "lightweight".
+  * the auxiliary load-balancing loss (aux_loss / aux_loss_bwd) is the product form
+    alpha * E * sum_e (load share of e) * (mean score share of e); the paper gives the
+    weight and a citation, not the formula.
 Every function works in the real type R (float64 unless told otherwise) on the
 input values widened to R; no intermediate is rounded to a narrower type.
 
@@ -112,6 +115,49 @@ def route_bwd(logits, idx, dw, gate="softmax", renorm=True, R=DEFAULT_R):
     if gate == "softmax":
         return s * (ds - (s * ds).sum(axis=1, keepdims=True))
     return ds * s * (1.0 - s)
+
+
+# ----------------------------------------------------------------- auxiliary loss
+def gate_shares(logits, gate, R=DEFAULT_R):
+    """The gate's scores as shares that sum to one over the E experts of a token:
+    the softmax itself, or the sigmoid scores divided by their sum."""
+    s = gate_scores(logits, gate, R)
+    return s if gate == "softmax" else s / s.sum(axis=1, keepdims=True)
+
+
+def aux_loss(logits, counts, k, alpha, gate="softmax", R=DEFAULT_R):
+    """Auxiliary load-balancing loss.  The evaluation setup of the paper trains with one
+    (weight 0.001, swept to 0.1 in its sensitivity study) and cites the GShard form without
+    printing it; the reading taken here is the usual product form of that family,
+
+        L = alpha * E * sum_e f_e * P_e,
+        f_e = counts[e] / (T k)   share of the T*k assignments that expert e received,
+        P_e = (1/T) sum_t p_te    mean share of expert e in the gate's scores,
+
+    which equals alpha whenever either the loads or the scores are uniform.
+    Returns (L, P[E])."""
+    p = gate_shares(logits, gate, R)
+    T, E = p.shape
+    f = np.asarray(counts).astype(R) / R(T * k)
+    P = p.sum(axis=0) / R(T)
+    return R(alpha) * R(E) * (f * P).sum(), P
+
+
+def aux_loss_bwd(logits, counts, k, alpha, gate="softmax", dloss=1.0, R=DEFAULT_R):
+    """d(aux_loss)/d(logits) [T, E], loads f held constant (they are piecewise constant in
+    the logits), times the upstream scalar dloss.
+        c_e = dL/dp_te = alpha E f_e / T                     (the same for every token)
+        softmax:  dz_te = p_te (c_e - sum_j p_tj c_j)
+        sigmoid:  p = s / S, S = sum_j s_j:  ds_te = (c_e - sum_j p_tj c_j) / S,
+                  dz_te = ds_te s_te (1 - s_te)"""
+    p = gate_shares(logits, gate, R)
+    T, E = p.shape
+    c = R(dloss) * R(alpha) * R(E) * (np.asarray(counts).astype(R) / R(T * k)) / R(T)
+    centred = c[None, :] - (p * c[None, :]).sum(axis=1, keepdims=True)
+    if gate == "softmax":
+        return p * centred
+    s = gate_scores(logits, gate, R)
+    return centred / s.sum(axis=1, keepdims=True) * s * (1.0 - s)
 
 
 # ------------------------------------------------------------------------- dispatch

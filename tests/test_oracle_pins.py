@@ -463,3 +463,102 @@ def test_planted_mistakes_are_caught(monkeypatch):
         m.setattr(orc, "swiglu_ffn_bwd", bad_bwd_swapped)
         assert not _pins_pass(), "exchanged dWg/dWu went unnoticed"
     assert _pins_pass()
+
+
+# ------------------------------------------------------------------ auxiliary load-balancing loss
+def _aux_pins():
+    """Closed forms, a hand-worked case, an independent torch evaluation with autograd, finite
+    differences and invariants of aux_loss / aux_loss_bwd."""
+    rng = np.random.default_rng(11)
+    alpha = 0.001
+    for gate in ("softmax", "sigmoid"):
+        # uniform scores: L = alpha whatever the loads
+        T, E, k = 12, 6, 2
+        counts = rng.multinomial(T * k, np.ones(E) / E)
+        L, P = orc.aux_loss(np.full((T, E), 0.7), counts, k, alpha, gate)
+        np.testing.assert_allclose(L, alpha, rtol=1e-14)
+        np.testing.assert_allclose(P, np.full(E, 1.0 / E), rtol=1e-14)
+        # uniform loads: L = alpha whatever the scores (the shares of a token sum to one)
+        L, P = orc.aux_loss(rng.normal(size=(T, E)), np.full(E, T * k // E), k, alpha, gate)
+        np.testing.assert_allclose(L, alpha, rtol=1e-13)
+        np.testing.assert_allclose(P.sum(), 1.0, rtol=1e-14)
+    # everything on one expert, top-1: L -> alpha * E
+    T, E = 5, 4
+    lg = np.zeros((T, E))
+    lg[:, 2] = 60.0
+    L, _ = orc.aux_loss(lg, np.array([0, 0, T, 0]), 1, alpha, "softmax")
+    np.testing.assert_allclose(L, alpha * E, rtol=1e-12)
+    # hand-worked: 2 tokens, 2 experts, top-1, logits (ln 3, 0) and (0, 0): shares (3/4, 1/4), (1/2, 1/2);
+    # P = (5/8, 3/8); counts (2, 0): f = (1, 0); L = alpha * 2 * 5/8
+    lg = np.array([[np.log(3.0), 0.0], [0.0, 0.0]])
+    L, P = orc.aux_loss(lg, np.array([2, 0]), 1, 1.0, "softmax")
+    np.testing.assert_allclose(P, [0.625, 0.375], rtol=1e-15)
+    np.testing.assert_allclose(L, 1.25, rtol=1e-15)
+    # gradient of that case: c = alpha E f / T = (1, 0); dz_t0 = p0 (1 - p0) = 3/16 and 1/4
+    g = orc.aux_loss_bwd(lg, np.array([2, 0]), 1, 1.0, "softmax")
+    np.testing.assert_allclose(g, [[3.0 / 16, -3.0 / 16], [0.25, -0.25]], rtol=1e-14)
+    # sigmoid gate, same logits: s = (3/4, 1/2), (1/2, 1/2): shares (3/5, 2/5), (1/2, 1/2); P0 = 11/20
+    L, P = orc.aux_loss(lg, np.array([2, 0]), 1, 1.0, "sigmoid")
+    np.testing.assert_allclose(P, [0.55, 0.45], rtol=1e-15)
+    np.testing.assert_allclose(L, 1.1, rtol=1e-15)
+    for gate in ("softmax", "sigmoid"):
+        T, E, k = 9, 7, 3
+        lg = rng.normal(size=(T, E)) * 2.0
+        counts = rng.multinomial(T * k, rng.dirichlet(np.ones(E)))
+        # independent evaluation in torch, differentiated by autograd
+        tz = torch.tensor(lg, requires_grad=True)
+        if gate == "softmax":
+            tp = torch.softmax(tz, dim=1)
+        else:
+            ts = torch.sigmoid(tz)
+            tp = ts / ts.sum(dim=1, keepdim=True)
+        tf = torch.tensor(counts, dtype=torch.float64) / (T * k)
+        tL = 0.3 * E * (tf * tp.mean(dim=0)).sum()
+        L, _ = orc.aux_loss(lg, counts, k, 0.3, gate)
+        np.testing.assert_allclose(L, tL.item(), rtol=1e-13)
+        (tL * 1.7).backward()
+        g = orc.aux_loss_bwd(lg, counts, k, 0.3, gate, dloss=1.7)
+        np.testing.assert_allclose(g, tz.grad.numpy(), rtol=1e-11, atol=1e-15)
+        # central finite differences on a few entries
+        h = 1e-6
+        for (t, e) in ((0, 0), (4, 3), (8, 6)):
+            zp, zm = lg.copy(), lg.copy()
+            zp[t, e] += h
+            zm[t, e] -= h
+            fd = (orc.aux_loss(zp, counts, k, 0.3, gate)[0] - orc.aux_loss(zm, counts, k, 0.3, gate)[0]) / (2 * h)
+            np.testing.assert_allclose(g[t, e] / 1.7, fd, rtol=1e-6, atol=1e-10)
+        if gate == "softmax":  # a shift of a token's logits changes nothing
+            np.testing.assert_allclose(g.sum(axis=1), 0.0, atol=1e-15)
+
+
+def test_aux_loss_pins():
+    _aux_pins()
+
+
+def test_planted_mistakes_in_aux_loss_are_caught(monkeypatch):
+    real_loss, real_bwd, real_shares = orc.aux_loss, orc.aux_loss_bwd, orc.gate_shares
+
+    def loss_per_token(logits, counts, k, alpha, gate="softmax", R=np.float64):  # loads divided by T, not T k
+        L, P = real_loss(logits, counts, k, alpha, gate, R)
+        return L * k, P
+
+    def loss_no_E(logits, counts, k, alpha, gate="softmax", R=np.float64):  # factor E dropped
+        L, P = real_loss(logits, counts, k, alpha, gate, R)
+        return L / np.asarray(logits).shape[1], P
+
+    def bwd_not_centred(logits, counts, k, alpha, gate="softmax", dloss=1.0, R=np.float64):  # - sum_j p_j c_j dropped
+        p = real_shares(logits, gate, R)
+        T, E = p.shape
+        c = dloss * alpha * E * (np.asarray(counts) / (T * k)) / T
+        return p * c[None, :]
+
+    def shares_unnormalised(logits, gate, R=np.float64):  # sigmoid scores not divided by their sum
+        return orc.gate_scores(logits, gate, R)
+
+    for name, bad in (("aux_loss", loss_per_token), ("aux_loss", loss_no_E), ("aux_loss_bwd", bwd_not_centred),
+                      ("gate_shares", shares_unnormalised)):
+        with monkeypatch.context() as m:
+            m.setattr(orc, name, bad)
+            with pytest.raises(AssertionError):
+                _aux_pins()
+    _aux_pins()
