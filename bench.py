@@ -160,7 +160,8 @@ def main():
     weights = wl.make_weights(cfg, dev)
     g = {k: v.to(dev) for k, v in inp.items()}
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
-    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, overlap_shared=args.overlap_shared)
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, overlap_shared=args.overlap_shared,
+                        aux_alpha=cfg.aux_alpha)
     sh = [weights.get("Wsg"), weights.get("Wsu"), weights.get("Wsd")]
 
     def step():

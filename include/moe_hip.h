@@ -122,6 +122,30 @@ int moe_route_bwd(const moe_shape_t* shape, const float* logits, const int32_t* 
                   float* dlogits, void* stream);
 
 /*
+ * moe_aux_loss / moe_aux_loss_bwd -- the auxiliary load-balancing loss the paper's evaluation
+ * setup trains with (Section 6, experimental setup: weight 0.001; its sensitivity study sweeps the
+ * weight to 0.1).  The paper cites the loss and does not print it; this is the product form of that
+ * family:
+ *   L = alpha * E * sum_e f_e * P_e,   f_e = counts[e] / (T k),   P_e = (1/T) sum_t p_te,
+ *   p_t = the gate's scores as shares of one: softmax(logits_t), or sigmoid(logits_t) divided by
+ *   its sum over the E experts.  L = alpha when the loads or the scores are uniform.
+ * The backward holds the loads f constant (they are piecewise constant in the logits):
+ *   c_e = dloss alpha E f_e / T;  softmax: dlogits_te = p_te (c_e - sum_j p_tj c_j);
+ *   sigmoid: dlogits_te = (c_e - sum_j p_tj c_j) / (sum_j s_tj) * s_te (1 - s_te).
+ *   logits [T, E] f32 (device);  counts [E] i32 (device, from moe_dispatch);  alpha, dloss host scalars
+ *   P [E] f32 out, loss [1] f32 out (device; both 0 when T == 0)
+ *   ws >= moe_aux_loss_workspace_bytes(shape): per-wavefront partial sums, reduced in a fixed
+ *   order (no atomics: two runs give identical bits)
+ *   dlogits [T, E] f32: written, or added to when accumulate != 0 (e.g. after moe_route_bwd)
+ * shape->renorm and shape->k's selection play no part beyond k in f_e.
+ */
+size_t moe_aux_loss_workspace_bytes(const moe_shape_t* shape);
+int moe_aux_loss(const moe_shape_t* shape, const float* logits, const int32_t* counts, float alpha, float* P,
+                 float* loss, void* ws, size_t ws_bytes, void* stream);
+int moe_aux_loss_bwd(const moe_shape_t* shape, const float* logits, const int32_t* counts, float alpha,
+                     float dloss, int32_t accumulate, float* dlogits, void* stream);
+
+/*
  * moe_dispatch -- group the T*k token-expert assignments by expert and copy the token rows
  * into expert-contiguous order (the local-dispatch case of Algorithm 3: counts[e] is its
  * token assignment T[e, d] for this device; no token is dropped).

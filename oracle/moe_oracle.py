@@ -355,8 +355,10 @@ def compact(dense, active_ids, n_active):
 
 # ---------------------------------------------------------------------- whole layer
 def layer_fwd_bwd(logits, X, dY, Wg, Wu, Wd, k, gate="softmax", renorm=True,
-                  Wsg=None, Wsu=None, Wsd=None, R=DEFAULT_R, want_dlogits=False):
-    """One forward and backward pass of the layer; returns every intermediate by name."""
+                  Wsg=None, Wsu=None, Wsd=None, R=DEFAULT_R, want_dlogits=False, aux_alpha=0.0):
+    """One forward and backward pass of the layer; returns every intermediate by name.
+    With aux_alpha > 0 the auxiliary load-balancing loss is evaluated too and its gradient
+    (upstream gradient 1) is part of dlogits."""
     E = len(Wg)
     X = np.asarray(X).astype(R)
     dY = np.asarray(dY).astype(R)
@@ -369,6 +371,8 @@ def layer_fwd_bwd(logits, X, dY, Wg, Wu, Wd, k, gate="softmax", renorm=True,
     if shared:
         o["Gs"], o["Us"], o["Ysh"] = shared_fwd(X, Wsg, Wsu, Wsd, R)
     o["Y"] = combine(o["Yp"], o["row_of"], o["topk_w"], o.get("Ysh"), R)
+    if aux_alpha > 0:
+        o["aux_loss"], o["aux_P"] = aux_loss(logits, o["counts"], k, aux_alpha, gate, R)
     # backward
     o["dYp"], o["dw"] = combine_bwd(dY, o["Yp"], o["row_of"], o["topk_w"], R)
     (o["dXp"], o["dWg"], o["dWu"], o["dWd"], o["dG"], o["dU"]) = expert_bwd(
@@ -379,6 +383,8 @@ def layer_fwd_bwd(logits, X, dY, Wg, Wu, Wd, k, gate="softmax", renorm=True,
     o["dX"] = unpermute(o["dXp"], o["row_of"], k, o.get("dXsh"), R)
     if want_dlogits:
         o["dlogits"] = route_bwd(logits, o["topk_idx"], o["dw"], gate, renorm, R)
+        if aux_alpha > 0:
+            o["dlogits"] = o["dlogits"] + aux_loss_bwd(logits, o["counts"], k, aux_alpha, gate, 1.0, R)
     return o
 
 

@@ -17,7 +17,8 @@ MOE_GATE_SOFTMAX, MOE_GATE_SIGMOID = 0, 1
 EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd", "moe_router_bwd",
            "moe_router_fwd_workspace_bytes", "moe_router_bwd_workspace_bytes", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
-           "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe"]
+           "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
+           "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd"]
 
 
 class MoEError(RuntimeError):
@@ -75,9 +76,13 @@ def load_library():
         f.argtypes = [shp, i32, i32, i32]
     lib.moe_route.restype = ctypes.c_int
     lib.moe_route.argtypes = [shp, vp, vp, vp, vp]
-    for f in (lib.moe_router_fwd_workspace_bytes, lib.moe_router_bwd_workspace_bytes):
+    for f in (lib.moe_router_fwd_workspace_bytes, lib.moe_router_bwd_workspace_bytes, lib.moe_aux_loss_workspace_bytes):
         f.restype = sz
         f.argtypes = [shp]
+    lib.moe_aux_loss.restype = ctypes.c_int
+    lib.moe_aux_loss.argtypes = [shp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
+    lib.moe_aux_loss_bwd.restype = ctypes.c_int
+    lib.moe_aux_loss_bwd.argtypes = [shp, vp, vp, ctypes.c_float, ctypes.c_float, i32, vp, vp]
     lib.moe_router_fwd.restype = ctypes.c_int
     lib.moe_router_fwd.argtypes = [shp, vp, vp, vp, vp, sz, vp]
     lib.moe_router_bwd.restype = ctypes.c_int
@@ -186,6 +191,25 @@ def moe_route_bwd(shape: MoEShape, logits, topk_idx, dw, dlogits, stream=None):
     _check(rc, "moe_route_bwd")
 
 
+def moe_aux_loss_workspace_bytes(shape: MoEShape) -> int:
+    return int(load_library().moe_aux_loss_workspace_bytes(ctypes.byref(shape.c())))
+
+
+def moe_aux_loss(shape: MoEShape, logits, counts, alpha, P, loss, ws, stream=None):
+    rc = load_library().moe_aux_loss(ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"),
+                                     _ptr(counts, torch.int32, "counts"), float(alpha), _ptr(P, torch.float32, "P"),
+                                     _ptr(loss, torch.float32, "loss"), _ptr(ws, None, "ws"),
+                                     ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_aux_loss")
+
+
+def moe_aux_loss_bwd(shape: MoEShape, logits, counts, alpha, dloss, accumulate, dlogits, stream=None):
+    rc = load_library().moe_aux_loss_bwd(ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"),
+                                         _ptr(counts, torch.int32, "counts"), float(alpha), float(dloss),
+                                         int(bool(accumulate)), _ptr(dlogits, torch.float32, "dlogits"), _stream(stream))
+    _check(rc, "moe_aux_loss_bwd")
+
+
 def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, ws, stream=None):
     dt = shape.torch_dtype
     rc = load_library().moe_dispatch(ctypes.byref(shape.c()), _ptr(X, dt, "X"), _ptr(topk_idx, torch.int32, "topk_idx"),
@@ -265,6 +289,8 @@ class MoEHotPath:
     forward():  moe_route -> moe_dispatch -> moe_expert_fwd (routed, then shared) -> moe_combine
     backward(): moe_combine_bwd -> moe_expert_bwd (routed, then shared) -> moe_combine (unit weights)
                 -> moe_route_bwd (gradient of the router logits)
+    With aux_alpha > 0, forward() also evaluates the auxiliary load-balancing loss (moe_aux_loss, after
+    the dispatch has counted the loads) and backward() adds its gradient to dlogits (moe_aux_loss_bwd).
     No arithmetic happens here; tensors are only allocated and handed to the library.
 
     The shared experts depend on nothing the routed experts produce, so with overlap_shared their
@@ -274,8 +300,9 @@ class MoEHotPath:
     """
 
     def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0",
-                 overlap_shared: bool = False):
+                 overlap_shared: bool = False, aux_alpha: float = 0.0):
         self.shape, self.S, self.Fs, self.device = shape, n_shared, d_ff_shared, torch.device(device)
+        self.aux_alpha = float(aux_alpha)
         self.overlap = bool(overlap_shared and n_shared)
         s, dt, dev = shape, shape.torch_dtype, self.device
         A = s.T * s.k
@@ -308,6 +335,10 @@ class MoEHotPath:
             })
             ws = max(ws, moe_expert_fwd_workspace_bytes(self.sshape, S, s.T, True),
                      moe_expert_bwd_workspace_bytes(self.sshape, S, s.T, True))
+        if self.aux_alpha > 0:
+            self.b.update({"aux_P": torch.empty(s.E, dtype=torch.float32, device=dev),
+                           "aux_loss": torch.empty(1, dtype=torch.float32, device=dev)})
+            ws = max(ws, moe_aux_loss_workspace_bytes(s))
         self.ws = torch.empty(ws, dtype=torch.uint8, device=dev)
         self.ws_shared = self.ws
         if self.overlap:  # concurrent calls need a workspace each
@@ -338,6 +369,8 @@ class MoEHotPath:
                            self.ws_shared, self.side)
         moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
         moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
+        if self.aux_alpha > 0:
+            moe_aux_loss(s, logits, b["counts"], self.aux_alpha, b["aux_P"], b["aux_loss"], self.ws, stream)
         moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
         if self.overlap:
             self._join(main)
@@ -364,4 +397,6 @@ class MoEHotPath:
                            b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws, stream)
         moe_combine(s, b["dXp"], b["row_of"], None, b["dXsh"] if self.S else None, b["dX"], stream)
         moe_route_bwd(s, self._logits, b["topk_idx"], b["dw"], b["dlogits"], stream)
+        if self.aux_alpha > 0:
+            moe_aux_loss_bwd(s, self._logits, b["counts"], self.aux_alpha, 1.0, True, b["dlogits"], stream)
         return b["dX"]

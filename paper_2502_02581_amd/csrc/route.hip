@@ -156,7 +156,181 @@ __global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict_
   }
 }
 
+// ---- auxiliary load-balancing loss: L = alpha E sum_e f_e P_e, f_e = counts[e] / (T k),
+// P_e = mean over tokens of expert e's share of the gate's scores (softmax, or sigmoid scores
+// divided by their sum over the E experts).  Same mapping as route_kernel: one wavefront per token,
+// lane l holds experts l, l + 64, ...
+template <int R>
+__device__ __forceinline__ void gate_shares(const float* __restrict__ row, int lane, int E, int gate, float (&s)[R],
+                                            float (&p)[R], float& inv_tot) {
+  float v[R];
+#pragma unroll
+  for (int r = 0; r < R; r++) v[r] = lane + 64 * r < E ? row[lane + 64 * r] : -INFINITY;
+  float tot = 0.f;
+  if (gate == MOE_GATE_SOFTMAX) {
+    float m = v[0];
+#pragma unroll
+    for (int r = 1; r < R; r++) m = fmaxf(m, v[r]);
+    m = wave_max(m);
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+      s[r] = lane + 64 * r < E ? expf(v[r] - m) : 0.f;
+      tot += s[r];
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+      s[r] = lane + 64 * r < E ? 1.f / (1.f + expf(-v[r])) : 0.f;
+      tot += s[r];
+    }
+  }
+  inv_tot = 1.f / wave_sum(tot);
+#pragma unroll
+  for (int r = 0; r < R; r++) p[r] = s[r] * inv_tot;
+}
+
+// Wave w sums the shares of tokens w, w + n_waves, ... in that order and writes its E partial sums:
+// no atomics, the same result on every run.
+template <int R>
+__global__ __launch_bounds__(256) void aux_partial_kernel(const float* __restrict__ logits, float* __restrict__ partial,
+                                                          int T, int E, int gate, int n_waves) {
+  const int lane = threadIdx.x & 63;
+  const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (w >= n_waves) return;
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; r++) acc[r] = 0.f;
+  for (int t = w; t < T; t += n_waves) {
+    float s[R], p[R], inv_tot;
+    gate_shares<R>(logits + (size_t)t * E, lane, E, gate, s, p, inv_tot);
+#pragma unroll
+    for (int r = 0; r < R; r++) acc[r] += p[r];
+  }
+#pragma unroll
+  for (int r = 0; r < R; r++)
+    if (lane + 64 * r < E) partial[(size_t)w * E + lane + 64 * r] = acc[r];
+}
+
+// One block: P_e from the partial sums (ascending wave order), then the loss (ascending expert order).
+__global__ __launch_bounds__(1024) void aux_finish_kernel(const float* __restrict__ partial,
+                                                          const int32_t* __restrict__ counts, float* __restrict__ P,
+                                                          float* __restrict__ loss, int T, int E, int k, float alpha,
+                                                          int n_waves) {
+  __shared__ float term[MOE_MAX_EXPERTS];
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    float sum = 0.f;
+    for (int w = 0; w < n_waves; w++) sum += partial[(size_t)w * E + e];
+    const float pe = T > 0 ? sum / (float)T : 0.f;
+    P[e] = pe;
+    term[e] = T > 0 ? pe * ((float)counts[e] / ((float)T * (float)k)) : 0.f;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float sum = 0.f;
+    for (int e = 0; e < E; e++) sum += term[e];
+    *loss = alpha * (float)E * sum;
+  }
+}
+
+// dlogits (+)= dloss * dL/dlogits with the loads held constant:
+//   c_e = dloss alpha E f_e / T;  softmax: dz_e = p_e (c_e - sum_j p_j c_j);
+//   sigmoid (p = s / S): dz_e = (c_e - sum_j p_j c_j) / S * s_e (1 - s_e)
+template <int R>
+__global__ __launch_bounds__(256) void aux_bwd_kernel(const float* __restrict__ logits, const int32_t* __restrict__ counts,
+                                                      float* __restrict__ dlogits, int T, int E, int k, int gate,
+                                                      float scale, int accumulate) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float s[R], p[R], inv_tot;
+  gate_shares<R>(logits + (size_t)t * E, lane, E, gate, s, p, inv_tot);
+  float c[R], dot = 0.f;
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    c[r] = lane + 64 * r < E ? scale * (float)counts[lane + 64 * r] : 0.f;
+    dot += p[r] * c[r];
+  }
+  dot = wave_sum(dot);
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    const int e = lane + 64 * r;
+    if (e < E) {
+      const float dz = gate == MOE_GATE_SOFTMAX ? p[r] * (c[r] - dot) : (c[r] - dot) * inv_tot * s[r] * (1.f - s[r]);
+      float* o = dlogits + (size_t)t * E + e;
+      *o = accumulate ? *o + dz : dz;
+    }
+  }
+}
+
+static int aux_waves(int T) { return T < 1024 ? T : 1024; }
+
 }  // namespace moe
+
+extern "C" size_t moe_aux_loss_workspace_bytes(const moe_shape_t* shape) {
+  if (!shape || shape->T < 0 || shape->E < 1) return 0;
+  return (size_t)moe::aux_waves(shape->T) * (size_t)shape->E * sizeof(float) + 256;
+}
+
+#define MOE_BY_EXPERTS(E, CALL) \
+  do {                          \
+    if ((E) <= 64) CALL(1);     \
+    else if ((E) <= 128) CALL(2); \
+    else if ((E) <= 256) CALL(4); \
+    else if ((E) <= 512) CALL(8); \
+    else CALL(16);              \
+  } while (0)
+
+extern "C" int moe_aux_loss(const moe_shape_t* shape, const float* logits, const int32_t* counts, float alpha, float* P,
+                            float* loss, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_aux_loss");
+  if (rc) return rc;
+  if (!P || !loss || (shape->T > 0 && (!logits || !counts || !ws))) {
+    set_error("moe_aux_loss: null pointer");
+    return MOE_EINVAL;
+  }
+  if (ws_bytes < moe_aux_loss_workspace_bytes(shape)) {
+    set_error("moe_aux_loss: workspace of %zu bytes, need %zu", ws_bytes, moe_aux_loss_workspace_bytes(shape));
+    return MOE_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int T = shape->T, E = shape->E, n_waves = aux_waves(T);
+  float* partial = (float*)ws;
+  ProfScope prof("aux_loss", st);
+  if (n_waves > 0) {
+    dim3 grid((n_waves + 3) / 4), block(256);
+#define MOE_AUX_PARTIAL(R) \
+  hipLaunchKernelGGL(aux_partial_kernel<R>, grid, block, 0, st, logits, partial, T, E, shape->gate, n_waves)
+    MOE_BY_EXPERTS(E, MOE_AUX_PARTIAL);
+#undef MOE_AUX_PARTIAL
+  }
+  hipLaunchKernelGGL(aux_finish_kernel, dim3(1), dim3(1024), 0, st, partial, counts, P, loss, T, E, shape->k, alpha, n_waves);
+  return launch_status("moe_aux_loss");
+}
+
+extern "C" int moe_aux_loss_bwd(const moe_shape_t* shape, const float* logits, const int32_t* counts, float alpha,
+                                float dloss, int32_t accumulate, float* dlogits, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_aux_loss_bwd");
+  if (rc) return rc;
+  if (shape->T == 0) return MOE_OK;  // nothing to do (empty tensors may be null)
+  if (!logits || !counts || !dlogits) {
+    set_error("moe_aux_loss_bwd: null pointer");
+    return MOE_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int T = shape->T, E = shape->E;
+  // c_e = scale * counts[e]
+  const float scale = dloss * alpha * (float)E / ((float)T * (float)shape->k) / (float)T;
+  dim3 grid((T + 3) / 4), block(256);
+  ProfScope prof("aux_loss_bwd", st);
+#define MOE_AUX_BWD(R) \
+  hipLaunchKernelGGL(aux_bwd_kernel<R>, grid, block, 0, st, logits, counts, dlogits, T, E, shape->k, shape->gate, scale, \
+                     (int)accumulate)
+  MOE_BY_EXPERTS(E, MOE_AUX_BWD);
+#undef MOE_AUX_BWD
+  return launch_status("moe_aux_loss_bwd");
+}
 
 extern "C" int moe_route_bwd(const moe_shape_t* shape, const float* logits, const int32_t* topk_idx, const float* dw,
                              float* dlogits, void* stream) {

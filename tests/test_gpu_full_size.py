@@ -44,7 +44,7 @@ def run_full(cfg):
     W = wl.make_weights(cfg, dev)
     g = {k: v.to(dev) for k, v in inp.items()}
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
-    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev)
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, aux_alpha=cfg.aux_alpha)
     sh = [W.get("Wsg"), W.get("Wsu"), W.get("Wsd")]
     hp.forward(g["logits"], g["X"], W["Wg"], W["Wu"], W["Wd"], *sh)
     hp.backward(g["dY"], g["X"], W["Wg"], W["Wu"], W["Wd"], *sh)
@@ -93,6 +93,11 @@ def test_full_size_sampled(name):
         ref_dw.append(dw)
     tt = torch.tensor(toks)
     ref_dlg = orc.route_bwd(lg[toks], idx[toks], np.stack(ref_dw), cfg.gate, cfg.renorm)
+    if cfg.aux_alpha > 0:  # the auxiliary loss and its share of dlogits need the loads of the whole batch
+        L_ref, P_ref = orc.aux_loss(lg, counts, cfg.k, cfg.aux_alpha, cfg.gate)
+        assert abs(float(b["aux_loss"].item()) - L_ref) <= 1e-4 * abs(L_ref)
+        assert scale_rel_err(b["aux_P"].cpu(), P_ref) <= 1e-4
+        ref_dlg = ref_dlg + orc.aux_loss_bwd(lg, counts, cfg.k, cfg.aux_alpha, cfg.gate)[toks]
     errs = {"Y": scale_rel_err(b["Y"].cpu()[tt], np.stack(ref_y)),
             "dX": scale_rel_err(b["dX"].cpu()[tt], np.stack(ref_dx)),
             "dw": scale_rel_err(b["dw"].cpu()[tt], np.stack(ref_dw)),

@@ -25,7 +25,7 @@ def hot_path(cfg):
     import paper_2502_02581_amd as moe
 
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
-    return moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared)
+    return moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, aux_alpha=cfg.aux_alpha)
 
 
 def run_gpu(cfg, p):
@@ -43,7 +43,7 @@ def run_gpu(cfg, p):
 def run_oracle(cfg, p):
     o = oracle_inputs(p)
     return orc.layer_fwd_bwd(o["logits"], o["X"], o["dY"], o["Wg"], o["Wu"], o["Wd"], cfg.k, cfg.gate, cfg.renorm,
-                             o.get("Wsg"), o.get("Wsu"), o.get("Wsd"), want_dlogits=True)
+                             o.get("Wsg"), o.get("Wsu"), o.get("Wsd"), want_dlogits=True, aux_alpha=cfg.aux_alpha)
 
 
 def compare_layer(cfg, got, ref):
@@ -61,6 +61,9 @@ def compare_layer(cfg, got, ref):
         fp += ["Ysh", "dXsh", "dWsg", "dWsu", "dWsd"]
     for key in fp:
         errs[key] = scale_rel_err(got[key], ref[key])
+    if cfg.aux_alpha > 0:
+        errs["aux_P"] = scale_rel_err(got["aux_P"], ref["aux_P"])
+        assert abs(float(got["aux_loss"][0]) - ref["aux_loss"]) <= 1e-4 * abs(ref["aux_loss"])
     if cfg.n_shared:
         errs["Gs"] = scale_rel_err(got["Gs"], ref["Gs"])
         errs["Us"] = scale_rel_err(got["Us"], ref["Us"])
@@ -80,6 +83,10 @@ LAYER_CASES = [
     (small_cfg("f32-sig", T=130, d=40, E=9, k=3, d_ff=56, dtype="f32", gate="sigmoid", zipf_s=1.5, n_shared=2,
                d_ff_shared=24), True),
     (small_cfg("f32-norenorm", T=64, d=32, E=5, k=2, d_ff=48, dtype="f32", renorm=False), True),
+    # auxiliary loss with a weight large enough for its share of dlogits to show at the tolerance
+    (small_cfg("f32-aux", T=300, d=72, E=6, k=2, d_ff=104, dtype="f32", zipf_s=1.0, aux_alpha=3000.0), True),
+    (small_cfg("bf16-aux-sig", T=400, d=192, E=20, k=4, d_ff=72, dtype="bf16", gate="sigmoid", zipf_s=1.5,
+               n_shared=1, d_ff_shared=136, aux_alpha=3000.0), True),
     # bf16 MFMA path: 128-row tiles with ragged tails in M, N and K
     (small_cfg("bf16-a", T=700, d=136, E=6, k=2, d_ff=200, dtype="bf16", zipf_s=1.0), True),
     (small_cfg("bf16-paper-scale", T=700, d=136, E=6, k=2, d_ff=200, dtype="bf16", zipf_s=1.0), False),
@@ -224,6 +231,57 @@ def test_route_bwd(E, k, gate, renorm):
     assert scale_rel_err(out.cpu(), ref) <= 1e-4
 
 
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (5, 64, 1), (203, 40, 3), (300, 65, 2), (1500, 256, 8), (2100, 300, 6),
+                                   (8192, 256, 8), (77, 1024, 64)])
+@pytest.mark.parametrize("gate", ["softmax", "sigmoid"])
+def test_aux_loss(T, E, k, gate):
+    """Auxiliary load-balancing loss, its per-expert mean shares and its gradient (written and accumulated)
+    against the oracle (fp32 arithmetic: 1e-4), with counts taken from the oracle's dispatch plan; the
+    partial sums are reduced in a fixed order, so a second run gives identical bits."""
+    import paper_2502_02581_amd as moe
+
+    cfg = small_cfg(T=T, d=8, E=E, k=k, d_ff=8, zipf_s=1.2, seed=9)
+    lg = wl.make_logits(cfg)
+    shape = moe.MoEShape(T, 8, E, k, 8, "f32", gate, True)
+    ridx, _ = orc.route(lg.numpy(), k, gate, True)
+    counts = orc.dispatch_plan(ridx, E)[0]
+    alpha, dloss = 0.01, 1.7
+    L_ref, P_ref = orc.aux_loss(lg.numpy(), counts, k, alpha, gate)
+    g_ref = orc.aux_loss_bwd(lg.numpy(), counts, k, alpha, gate, dloss)
+    dev = "cuda"
+    ws = torch.empty(moe.moe_aux_loss_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    c_dev = torch.from_numpy(counts).to(dev)
+    runs = []
+    for _ in range(2):
+        P = torch.full((E,), float("nan"), device=dev)
+        L = torch.full((1,), float("nan"), device=dev)
+        ws.fill_(255)
+        moe.moe_aux_loss(shape, lg.to(dev), c_dev, alpha, P, L, ws)
+        runs.append((P.cpu(), L.cpu()))
+    assert torch.equal(runs[0][0], runs[1][0]) and torch.equal(runs[0][1], runs[1][1])
+    assert scale_rel_err(runs[0][0], P_ref) <= 1e-4
+    assert abs(float(runs[0][1]) - L_ref) <= 1e-4 * abs(L_ref)
+    out = torch.full((T, E), float("nan"), device=dev)
+    moe.moe_aux_loss_bwd(shape, lg.to(dev), c_dev, alpha, dloss, False, out)
+    assert scale_rel_err(out.cpu(), g_ref) <= 1e-4
+    base = torch.randn(T, E, generator=torch.Generator().manual_seed(2)) * float(np.abs(g_ref).max())
+    acc = base.to(dev)
+    moe.moe_aux_loss_bwd(shape, lg.to(dev), c_dev, alpha, dloss, True, acc)
+    assert scale_rel_err(acc.cpu(), base.double().numpy() + g_ref) <= 1e-4
+
+
+def test_aux_loss_empty_batch():
+    import paper_2502_02581_amd as moe
+
+    shape = moe.MoEShape(0, 8, 6, 2, 8, "f32")
+    P = torch.full((6,), 5.0, device="cuda")
+    L = torch.full((1,), 5.0, device="cuda")
+    ws = torch.empty(max(1, moe.moe_aux_loss_workspace_bytes(shape)), dtype=torch.uint8, device="cuda")
+    moe.moe_aux_loss(shape, None, None, 0.01, P, L, ws)
+    moe.moe_aux_loss_bwd(shape, None, None, 0.01, 1.0, False, None)
+    assert not P.cpu().any() and float(L) == 0.0
+
+
 ROUTER_CASES = [
     # (T, d, E, dtype): fp32 path; general bf16 path (d not a multiple of 64); LDS-DMA path with E
     # not a multiple of 8, E a multiple of 64, E above one column tile
@@ -271,7 +329,7 @@ def test_overlap_shared_is_identical():
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
     outs = []
     for overlap in (False, True):
-        hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, "cuda:0", overlap_shared=overlap)
+        hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, "cuda:0", overlap_shared=overlap, aux_alpha=cfg.aux_alpha)
         for _ in range(3):  # repeated steps reuse the buffers and the events
             hp.forward(g["logits"], g["X"], g["Wg"], g["Wu"], g["Wd"], g["Wsg"], g["Wsu"], g["Wsd"])
             hp.backward(g["dY"], g["X"], g["Wg"], g["Wu"], g["Wd"], g["Wsg"], g["Wsu"], g["Wsd"])

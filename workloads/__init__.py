@@ -41,6 +41,7 @@ class MoEConfig:
     hot_frac: float = 0.30  # stress: share of tokens that select the hot expert
     n_zero: int = 10        # stress: experts that receive nothing
     seed: int = 0
+    aux_alpha: float = 0.0  # weight of the auxiliary load-balancing loss (0: not computed)
 
     @property
     def A(self) -> int:
@@ -63,16 +64,19 @@ class MoEConfig:
         }
 
 
+# every model of the paper's evaluation trains with an auxiliary load-balancing loss of this weight
+AUX_ALPHA = 0.001
+
 # The five layers BASELINE names.  Shapes d, d_ff, top-k follow Table 1 of the paper.
 CONFIGS: Dict[str, MoEConfig] = {
-    "tiny": MoEConfig("tiny", T=256, d=128, E=8, k=2, d_ff=256, dtype="f32", zipf_s=0.0),
+    "tiny": MoEConfig("tiny", T=256, d=128, E=8, k=2, d_ff=256, dtype="f32", zipf_s=0.0, aux_alpha=AUX_ALPHA),
     "qwen": MoEConfig("qwen", T=4096, d=2048, E=60, k=4, d_ff=1408, n_shared=4,
-                      d_ff_shared=1408, zipf_s=1.0),
-    "phi": MoEConfig("phi", T=8192, d=4096, E=16, k=2, d_ff=6400, zipf_s=0.8),
+                      d_ff_shared=1408, zipf_s=1.0, aux_alpha=AUX_ALPHA),
+    "phi": MoEConfig("phi", T=8192, d=4096, E=16, k=2, d_ff=6400, zipf_s=0.8, aux_alpha=AUX_ALPHA),
     "dsv3": MoEConfig("dsv3", T=8192, d=7168, E=256, k=8, d_ff=2048, n_shared=1,
-                      d_ff_shared=2048, gate="sigmoid", zipf_s=1.2),
+                      d_ff_shared=2048, gate="sigmoid", zipf_s=1.2, aux_alpha=AUX_ALPHA),
     "stress": MoEConfig("stress", T=16384, d=2048, E=60, k=4, d_ff=1408, routing="stress",
-                        zipf_s=1.5),
+                        zipf_s=1.5, aux_alpha=AUX_ALPHA),
 }
 
 WEIGHT_STD = 0.02
