@@ -211,15 +211,31 @@ __global__ __launch_bounds__(256) void aux_partial_kernel(const float* __restric
     if (lane + 64 * r < E) partial[(size_t)w * E + lane + 64 * r] = acc[r];
 }
 
-// One block: P_e from the partial sums (ascending wave order), then the loss (ascending expert order).
+// One block of 1024 threads: P_e from the partial sums, then the loss.  The waves are cut into C equal
+// runs (C = 1024 / E rounded down to a power of two); thread (c, e) adds run c of expert e in ascending
+// wave order, the C run sums are added in ascending c, the E terms of the loss in ascending e: a fixed
+// order throughout.
 __global__ __launch_bounds__(1024) void aux_finish_kernel(const float* __restrict__ partial,
                                                           const int32_t* __restrict__ counts, float* __restrict__ P,
                                                           float* __restrict__ loss, int T, int E, int k, float alpha,
                                                           int n_waves) {
+  __shared__ float part[1024];
   __shared__ float term[MOE_MAX_EXPERTS];
-  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+  int C = 1;
+  while (C * 2 * E <= 1024) C *= 2;
+  const int c = threadIdx.x / E, e = threadIdx.x - c * E;
+  if (c < C) {
+    const int per = (n_waves + C - 1) / C;
+    const int w0 = c * per, w1 = min(n_waves, w0 + per);
     float sum = 0.f;
-    for (int w = 0; w < n_waves; w++) sum += partial[(size_t)w * E + e];
+#pragma unroll 8
+    for (int w = w0; w < w1; w++) sum += partial[(size_t)w * E + e];
+    part[c * E + e] = sum;
+  }
+  __syncthreads();
+  if (threadIdx.x < E) {
+    float sum = 0.f;
+    for (int q = 0; q < C; q++) sum += part[q * E + e];
     const float pe = T > 0 ? sum / (float)T : 0.f;
     P[e] = pe;
     term[e] = T > 0 ? pe * ((float)counts[e] / ((float)T * (float)k)) : 0.f;
@@ -227,7 +243,7 @@ __global__ __launch_bounds__(1024) void aux_finish_kernel(const float* __restric
   __syncthreads();
   if (threadIdx.x == 0) {
     float sum = 0.f;
-    for (int e = 0; e < E; e++) sum += term[e];
+    for (int q = 0; q < E; q++) sum += term[q];
     *loss = alpha * (float)E * sum;
   }
 }
@@ -262,7 +278,7 @@ __global__ __launch_bounds__(256) void aux_bwd_kernel(const float* __restrict__ 
   }
 }
 
-static int aux_waves(int T) { return T < 1024 ? T : 1024; }
+static int aux_waves(int T) { return T < 256 ? T : 256; }
 
 }  // namespace moe
 
