@@ -243,6 +243,40 @@ size_t moe_profile_report(char* buf, size_t buf_bytes);
  */
 int moe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
 
+/*
+ * Host-side planners of the paper.  Every pointer below is HOST memory; nothing here touches the
+ * GPU.  E experts, D devices; devices n*dpn .. n*dpn + dpn - 1 form node n (D a multiple of dpn).
+ * A placement is an [E, D] matrix of bytes: nonzero = device d holds the parameters of expert e.
+ * All calls return MOE_OK or MOE_EINVAL (bad sizes, null pointers, negative or NaN loads,
+ * negative token counts, an expert held by no device); outputs are then unspecified.
+ *
+ * moe_plan_overlap_degree -- t = floor(T_attn * bw / Psi): the expert chunks of Psi bytes that a link
+ *   of bandwidth bw absorbs within the attention window T_attn (Section 4.2, after Algorithm 1);
+ *   clipped to INT32_MAX.
+ * moe_plan_predict_load -- the expert load estimate of Section 4.2: mean of the last min(w, n_iters)
+ *   rows of history [n_iters, E] (oldest first; the paper uses w = 5) into F [E].
+ * moe_plan_materialize -- Algorithm 1 (Sparse Materialization): from the shard placement P, the
+ *   loads F [E] (>= 0), the overlap degree t and the budget m of ephemeral replicas per device to
+ *   the plan P_out [E, D], a superset of P (P_out may be P).  t <- min(t, E), m <- min(m, t); the
+ *   top-t experts by load (descending, equal loads by ascending id) are candidates.  t <= m: each of
+ *   them goes to every device.  Otherwise, in descending load, expert e receives
+ *   n = max(1, floor(D m F[e] / sum of the top-t loads)) new replicas (0 if all those loads are 0;
+ *   at most one replica per device), placed one at a time on the device that lacks e, has a free
+ *   slot, and comes first by (its node already holds e, most free slots, lowest device id) -- the
+ *   paper names these two sub-steps without defining them; this is the reading taken.
+ * moe_plan_dispatch -- Algorithm 3 (Topology-aware Token Dispatching): from the placement Pm and
+ *   the token assignment T [E, D] (tokens of device d routed to expert e) to the plan
+ *   R [E, D, D], R[e, d, d2] = tokens of device d sent to expert e on device d2: everything stays
+ *   on d when d holds e; otherwise it is split evenly over the holders in d's node if there are
+ *   any, else over all holders (floor(x / n) each, one more to the first x mod n holders in
+ *   ascending device id).
+ */
+int moe_plan_overlap_degree(double t_attn, double bw, double psi, int32_t* t_out);
+int moe_plan_predict_load(const double* history, int32_t n_iters, int32_t E, int32_t w, double* F);
+int moe_plan_materialize(int32_t E, int32_t D, int32_t dpn, const uint8_t* P, const double* F, int32_t t, int32_t m,
+                         uint8_t* P_out);
+int moe_plan_dispatch(int32_t E, int32_t D, int32_t dpn, const uint8_t* Pm, const int32_t* T, int32_t* R);
+
 #ifdef __cplusplus
 }
 #endif

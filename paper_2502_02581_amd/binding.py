@@ -18,7 +18,8 @@ EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd
            "moe_router_fwd_workspace_bytes", "moe_router_bwd_workspace_bytes", "moe_dispatch_workspace_bytes", "moe_expert_fwd_workspace_bytes",
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
-           "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd"]
+           "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd",
+           "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch"]
 
 
 class MoEError(RuntimeError):
@@ -83,6 +84,15 @@ def load_library():
     lib.moe_aux_loss.argtypes = [shp, vp, vp, ctypes.c_float, vp, vp, vp, sz, vp]
     lib.moe_aux_loss_bwd.restype = ctypes.c_int
     lib.moe_aux_loss_bwd.argtypes = [shp, vp, vp, ctypes.c_float, ctypes.c_float, i32, vp, vp]
+    dbl = ctypes.c_double
+    lib.moe_plan_overlap_degree.restype = ctypes.c_int
+    lib.moe_plan_overlap_degree.argtypes = [dbl, dbl, dbl, ctypes.POINTER(ctypes.c_int32)]
+    lib.moe_plan_predict_load.restype = ctypes.c_int
+    lib.moe_plan_predict_load.argtypes = [vp, i32, i32, i32, vp]
+    lib.moe_plan_materialize.restype = ctypes.c_int
+    lib.moe_plan_materialize.argtypes = [i32, i32, i32, vp, vp, i32, i32, vp]
+    lib.moe_plan_dispatch.restype = ctypes.c_int
+    lib.moe_plan_dispatch.argtypes = [i32, i32, i32, vp, vp, vp]
     lib.moe_router_fwd.restype = ctypes.c_int
     lib.moe_router_fwd.argtypes = [shp, vp, vp, vp, vp, sz, vp]
     lib.moe_router_bwd.restype = ctypes.c_int
@@ -208,6 +218,63 @@ def moe_aux_loss_bwd(shape: MoEShape, logits, counts, alpha, dloss, accumulate, 
                                          _ptr(counts, torch.int32, "counts"), float(alpha), float(dloss),
                                          int(bool(accumulate)), _ptr(dlogits, torch.float32, "dlogits"), _stream(stream))
     _check(rc, "moe_aux_loss_bwd")
+
+
+# ---- host-side planners: numpy arrays in host memory, no GPU involved
+def _host(a, dtype, shape, what):
+    import numpy as np
+
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if a.shape != tuple(shape):
+        raise MoEError(f"{what} must have shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def moe_plan_overlap_degree(t_attn: float, bw: float, psi: float) -> int:
+    out = ctypes.c_int32(0)
+    _check(load_library().moe_plan_overlap_degree(float(t_attn), float(bw), float(psi), ctypes.byref(out)),
+           "moe_plan_overlap_degree")
+    return int(out.value)
+
+
+def moe_plan_predict_load(history, w: int = 5):
+    import numpy as np
+
+    h = np.ascontiguousarray(history, dtype=np.float64)
+    if h.ndim != 2:
+        raise MoEError("history must be [n_iters, E]")
+    F = np.empty(h.shape[1], dtype=np.float64)
+    _check(load_library().moe_plan_predict_load(h.ctypes.data, h.shape[0], h.shape[1], int(w), F.ctypes.data),
+           "moe_plan_predict_load")
+    return F
+
+
+def moe_plan_materialize(P, F, t: int, m: int, dpn: int):
+    import numpy as np
+
+    P = np.ascontiguousarray(P, dtype=np.uint8)
+    if P.ndim != 2:
+        raise MoEError("P must be [E, D]")
+    E, D = P.shape
+    F = _host(F, np.float64, (E,), "F")
+    out = np.empty_like(P)
+    _check(load_library().moe_plan_materialize(E, D, int(dpn), P.ctypes.data, F.ctypes.data, int(t), int(m),
+                                               out.ctypes.data), "moe_plan_materialize")
+    return out
+
+
+def moe_plan_dispatch(Pm, T, dpn: int):
+    import numpy as np
+
+    Pm = np.ascontiguousarray(Pm, dtype=np.uint8)
+    if Pm.ndim != 2:
+        raise MoEError("Pm must be [E, D]")
+    E, D = Pm.shape
+    T = _host(T, np.int32, (E, D), "T")
+    R = np.empty((E, D, D), dtype=np.int32)
+    _check(load_library().moe_plan_dispatch(E, D, int(dpn), Pm.ctypes.data, T.ctypes.data, R.ctypes.data),
+           "moe_plan_dispatch")
+    return R
 
 
 def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, ws, stream=None):

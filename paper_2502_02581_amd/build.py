@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
-SOURCES = ["common.hip", "route.hip", "dispatch.hip", "combine.hip", "expert.hip"]
+SOURCES = ["common.hip", "route.hip", "dispatch.hip", "combine.hip", "expert.hip", "planner.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
