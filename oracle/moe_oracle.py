@@ -10,7 +10,9 @@ with the expert body of Eq. 1 (FFN(x) = f(x W^A) W^B), evaluated exactly as the
 definition says and then differentiated by hand.  The readings the paper leaves
 open are taken as follows (each is a choice of this build, not of the paper):
   * f(x W^A) is SwiGLU: W^A is the pair (Wg, Wu), f(x W^A) = silu(x Wg) * (x Wu),
-    silu(z) = z / (1 + exp(-z));  W^B is Wd.
+    silu(z) = z / (1 + exp(-z));  W^B is Wd.  For the paper's synthetic GPT-MoE models (a
+    sparsified GPT-3: two matrices per expert, d_ffn = 4 d_model) Wu is None and f is GELU,
+    gelu(z) = z Phi(z); the paper does not name f.
   * g is a softmax over all E logits, or an element-wise sigmoid; the k selected
     scores are divided by their sum when renorm is set.
   * selection is on the raw fp32 logits (both gates are increasing in the logit):
@@ -38,6 +40,7 @@ pin comes from printed paper values.
 from __future__ import annotations
 
 import numpy as np
+from scipy.special import erf as _erf
 
 DEFAULT_R = np.float64
 
@@ -224,6 +227,48 @@ def swiglu_ffn_bwd(x, Wg, Wu, Wd, g, u, dy):
     return dx, x.T @ dg, x.T @ du, h.T @ dy, dg, du
 
 
+def gelu(z):
+    """x * Phi(x) with the standard normal distribution function Phi."""
+    return 0.5 * z * (1.0 + _erf(z / np.sqrt(2.0)))
+
+
+def gelu_ffn(x, Wa, Wb):
+    """Eq. 1 as printed, FFN(x) = f(x W^A) W^B, with f = GELU: returns (z, h, y) for rows x."""
+    z = x @ Wa
+    h = gelu(z)
+    return z, h, h @ Wb
+
+
+def gelu_ffn_bwd(x, Wa, Wb, z, dy):
+    """Chain rule on the two-matrix FFN: returns (dx, dWa, dWb, dz);
+    f'(z) = Phi(z) + z phi(z), phi the standard normal density."""
+    dh = dy @ Wb.T
+    dz = dh * (0.5 * (1.0 + _erf(z / np.sqrt(2.0))) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi))
+    return dz @ Wa.T, x.T @ dz, gelu(z).T @ dy, dz
+
+
+def ffn(x, Wg, Wu, Wd):
+    """The expert body: SwiGLU with three matrices, or (Wu is None) the two-matrix GELU FFN
+    with W^A = Wg, W^B = Wd.  Returns (g, u, h, y); in the two-matrix case g is the
+    pre-activation and u is zero."""
+    if Wu is None:
+        z, h, y = gelu_ffn(x, Wg, Wd)
+        return z, np.zeros_like(z), h, y
+    return swiglu_ffn(x, Wg, Wu, Wd)
+
+
+def ffn_bwd(x, Wg, Wu, Wd, g, u, dy):
+    """Returns (dx, dWg, dWu, dWd, dg, du); dWu and du are zero in the two-matrix case."""
+    if Wu is None:
+        dx, dWa, dWb, dz = gelu_ffn_bwd(x, Wg, Wd, g, dy)
+        return dx, dWa, np.zeros_like(dWa), dWb, dz, np.zeros_like(dz)
+    return swiglu_ffn_bwd(x, Wg, Wu, Wd, g, u, dy)
+
+
+def _mat(W, i, R):
+    return None if W is None else np.asarray(W[i]).astype(R)
+
+
 def expert_fwd(Xp, offsets, Wg, Wu, Wd, R=DEFAULT_R):
     """Every expert on its own contiguous block of rows; experts without rows do nothing."""
     Xp = np.asarray(Xp).astype(R)
@@ -238,8 +283,7 @@ def expert_fwd(Xp, offsets, Wg, Wu, Wd, R=DEFAULT_R):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         if hi == lo:
             continue
-        g, u, h, y = swiglu_ffn(Xp[lo:hi], np.asarray(Wg[e]).astype(R), np.asarray(Wu[e]).astype(R),
-                                np.asarray(Wd[e]).astype(R))
+        g, u, h, y = ffn(Xp[lo:hi], _mat(Wg, e, R), _mat(Wu, e, R), _mat(Wd, e, R))
         G[lo:hi], U[lo:hi], H[lo:hi], Yp[lo:hi] = g, u, h, y
     return G, U, H, Yp
 
@@ -261,9 +305,8 @@ def expert_bwd(Xp, offsets, Wg, Wu, Wd, G, U, dYp, R=DEFAULT_R):
         lo, hi = int(offsets[e]), int(offsets[e + 1])
         if hi == lo:
             continue
-        out = swiglu_ffn_bwd(Xp[lo:hi], np.asarray(Wg[e]).astype(R), np.asarray(Wu[e]).astype(R),
-                             np.asarray(Wd[e]).astype(R), np.asarray(G[lo:hi]).astype(R),
-                             np.asarray(U[lo:hi]).astype(R), dYp[lo:hi])
+        out = ffn_bwd(Xp[lo:hi], _mat(Wg, e, R), _mat(Wu, e, R), _mat(Wd, e, R), np.asarray(G[lo:hi]).astype(R),
+                      np.asarray(U[lo:hi]).astype(R), dYp[lo:hi])
         dXp[lo:hi], dWg[e], dWu[e], dWd[e], dG[lo:hi], dU[lo:hi] = out
     return dXp, dWg, dWu, dWd, dG, dU
 
@@ -275,8 +318,7 @@ def shared_fwd(X, Wsg, Wsu, Wsd, R=DEFAULT_R):
     Gs, Us = [], []
     Ysh = np.zeros_like(X)
     for s in range(S):
-        g, u, _, y = swiglu_ffn(X, np.asarray(Wsg[s]).astype(R), np.asarray(Wsu[s]).astype(R),
-                                np.asarray(Wsd[s]).astype(R))
+        g, u, _, y = ffn(X, _mat(Wsg, s, R), _mat(Wsu, s, R), _mat(Wsd, s, R))
         Gs.append(g)
         Us.append(u)
         Ysh += y
@@ -291,9 +333,8 @@ def shared_bwd(X, Wsg, Wsu, Wsd, Gs, Us, dY, R=DEFAULT_R):
     dX = np.zeros_like(X)
     dWsg, dWsu, dWsd = [], [], []
     for s in range(S):
-        dx, a, b, c, _, _ = swiglu_ffn_bwd(X, np.asarray(Wsg[s]).astype(R), np.asarray(Wsu[s]).astype(R),
-                                           np.asarray(Wsd[s]).astype(R), np.asarray(Gs[s]).astype(R),
-                                           np.asarray(Us[s]).astype(R), dY)
+        dx, a, b, c, _, _ = ffn_bwd(X, _mat(Wsg, s, R), _mat(Wsu, s, R), _mat(Wsd, s, R), np.asarray(Gs[s]).astype(R),
+                                    np.asarray(Us[s]).astype(R), dY)
         dX += dx
         dWsg.append(a)
         dWsu.append(b)
@@ -400,15 +441,15 @@ def token_fwd_bwd(x, idx_t, w_t, dy, Wg, Wu, Wd, Wsg=None, Wsu=None, Wsd=None, R
     dx = np.zeros_like(x)
     dw = np.zeros(len(idx_t), dtype=R)
     for j, e in enumerate(idx_t):
-        We = [np.asarray(W[int(e)]).astype(R) for W in (Wg, Wu, Wd)]
-        g, u, _, yj = swiglu_ffn(x, *We)
+        We = [_mat(W, int(e), R) for W in (Wg, Wu, Wd)]
+        g, u, _, yj = ffn(x, *We)
         y += R(w_t[j]) * yj
         dw[j] = float((dy * yj).sum())
-        dx += swiglu_ffn_bwd(x, *We, g, u, R(w_t[j]) * dy)[0]
+        dx += ffn_bwd(x, *We, g, u, R(w_t[j]) * dy)[0]
     if Wsg is not None:
         for s in range(len(Wsg)):
-            We = [np.asarray(W[s]).astype(R) for W in (Wsg, Wsu, Wsd)]
-            g, u, _, ys = swiglu_ffn(x, *We)
+            We = [_mat(W, s, R) for W in (Wsg, Wsu, Wsd)]
+            g, u, _, ys = ffn(x, *We)
             y += ys
-            dx += swiglu_ffn_bwd(x, *We, g, u, dy)[0]
+            dx += ffn_bwd(x, *We, g, u, dy)[0]
     return y[0], dx[0], dw

@@ -13,10 +13,10 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
 def small_cfg(name="t", T=24, d=8, E=6, k=2, d_ff=12, n_shared=0, d_ff_shared=0, dtype="f32",
-              gate="softmax", renorm=True, zipf_s=1.0, seed=0, routing="zipf", aux_alpha=0.0):
+              gate="softmax", renorm=True, zipf_s=1.0, seed=0, routing="zipf", aux_alpha=0.0, ffn="swiglu"):
     return wl.MoEConfig(name, T=T, d=d, E=E, k=k, d_ff=d_ff, n_shared=n_shared, d_ff_shared=d_ff_shared,
                         dtype=dtype, gate=gate, renorm=renorm, zipf_s=zipf_s, seed=seed, routing=routing,
-                        aux_alpha=aux_alpha)
+                        aux_alpha=aux_alpha, ffn=ffn)
 
 
 def np64(t):

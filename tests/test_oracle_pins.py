@@ -562,3 +562,83 @@ def test_planted_mistakes_in_aux_loss_are_caught(monkeypatch):
             with pytest.raises(AssertionError):
                 _aux_pins()
     _aux_pins()
+
+
+# ------------------------------------------------------------ two-matrix GELU expert (Eq. 1 as printed)
+def _gelu_pins():
+    # closed forms: gelu(z) = z Phi(z); Phi(1) = 0.8413447460685429 (standard normal table value)
+    z = np.array([0.0, 1.0, -1.0, 8.0])
+    np.testing.assert_allclose(orc.gelu(z), [0.0, 0.8413447460685429, -0.15865525393145707, 8.0], rtol=1e-14, atol=1e-14)
+    # a 1x1 "expert": y = gelu(x a) b;  dy/dx at z = 0 is a b / 2, at z = 1 it is a b (Phi(1) + phi(1))
+    for zz, slope in ((0.0, 0.5), (1.0, 0.8413447460685429 + 0.24197072451914337)):
+        x, a, b = np.array([[1.0]]), np.array([[zz]]), np.array([[3.0]])
+        zv, h, y = orc.gelu_ffn(x, a, b)
+        dx, dWa, dWb, dz = orc.gelu_ffn_bwd(x, a, b, zv, np.array([[1.0]]))
+        np.testing.assert_allclose(dz, [[3.0 * slope]], rtol=1e-14)
+        np.testing.assert_allclose(dx, [[3.0 * slope * zz]], rtol=1e-14, atol=1e-15)
+        np.testing.assert_allclose(dWa, [[3.0 * slope]], rtol=1e-14)
+        np.testing.assert_allclose(dWb, h, rtol=1e-14)
+    # the whole layer with two matrices per expert against a dense masked evaluation in torch
+    for cfg in (small_cfg(T=24, d=8, E=6, k=2, d_ff=12, ffn="gelu"),
+                small_cfg(T=16, d=8, E=5, k=3, d_ff=6, ffn="gelu", gate="sigmoid", n_shared=2, d_ff_shared=7)):
+        p = problem(cfg)
+        assert "Wu" not in p and "Wsu" not in p
+        o = oracle_inputs(p)
+        out = orc.layer_fwd_bwd(o["logits"], o["X"], o["dY"], o["Wg"], None, o["Wd"], cfg.k, cfg.gate, cfg.renorm,
+                                o.get("Wsg"), None, o.get("Wsd"), want_dlogits=True)
+        tX = torch.tensor(o["X"], requires_grad=True)
+        tWa = torch.tensor(o["Wg"], requires_grad=True)
+        tWb = torch.tensor(o["Wd"], requires_grad=True)
+        tw = torch.tensor(out["topk_w"], requires_grad=True)
+        wfull = torch.zeros(cfg.T, cfg.E, dtype=torch.float64).scatter(1, torch.tensor(out["topk_idx"].astype(np.int64)), tw)
+        Y = torch.zeros(cfg.T, cfg.d, dtype=torch.float64)
+        for e in range(cfg.E):
+            Y = Y + wfull[:, e:e + 1] * (torch.nn.functional.gelu(tX @ tWa[e]) @ tWb[e])
+        shared = {}
+        if cfg.n_shared:
+            shared = {n: torch.tensor(o[n], requires_grad=True) for n in ("Wsg", "Wsd")}
+            for s_ in range(cfg.n_shared):
+                Y = Y + torch.nn.functional.gelu(tX @ shared["Wsg"][s_]) @ shared["Wsd"][s_]
+        (Y * torch.tensor(o["dY"])).sum().backward()
+        tol = dict(rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(out["Y"], Y.detach().numpy(), **tol)
+        np.testing.assert_allclose(out["dX"], tX.grad.numpy(), **tol)
+        np.testing.assert_allclose(out["dWg"], tWa.grad.numpy(), **tol)
+        np.testing.assert_allclose(out["dWd"], tWb.grad.numpy(), **tol)
+        np.testing.assert_allclose(out["dw"], tw.grad.numpy(), **tol)
+        assert not out["dWu"].any() and not out["U"].any()
+        if cfg.n_shared:
+            np.testing.assert_allclose(out["dWsg"], shared["Wsg"].grad.numpy(), **tol)
+            np.testing.assert_allclose(out["dWsd"], shared["Wsd"].grad.numpy(), **tol)
+    # one expert, top-1: two plain matrix products around the activation
+    cfg = small_cfg(T=10, d=6, E=1, k=1, d_ff=9, ffn="gelu")
+    o = oracle_inputs(problem(cfg))
+    out = orc.layer_fwd_bwd(o["logits"], o["X"], o["dY"], o["Wg"], None, o["Wd"], 1)
+    np.testing.assert_allclose(out["Y"], orc.gelu(o["X"] @ o["Wg"][0]) @ o["Wd"][0], rtol=1e-12, atol=1e-14)
+
+
+def test_two_matrix_gelu_ffn():
+    _gelu_pins()
+
+
+def test_planted_mistakes_in_gelu_ffn_are_caught(monkeypatch):
+    real_bwd, real_gelu = orc.gelu_ffn_bwd, orc.gelu
+
+    def bwd_without_density_term(x, Wa, Wb, z, dy):      # f'(z) = Phi(z) only
+        from scipy.special import erf
+        dz = (dy @ Wb.T) * 0.5 * (1.0 + erf(z / np.sqrt(2.0)))
+        return dz @ Wa.T, x.T @ dz, real_gelu(z).T @ dy, dz
+
+    def tanh_gelu(z):                                     # the tanh approximation instead of z Phi(z)
+        return 0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)))
+
+    def bwd_swapped(x, Wa, Wb, z, dy):                    # dWb from the pre-activation instead of the activation
+        dx, dWa, _, dz = real_bwd(x, Wa, Wb, z, dy)
+        return dx, dWa, z.T @ dy, dz
+
+    for name, bad in (("gelu_ffn_bwd", bwd_without_density_term), ("gelu", tanh_gelu), ("gelu_ffn_bwd", bwd_swapped)):
+        with monkeypatch.context() as m:
+            m.setattr(orc, name, bad)
+            with pytest.raises(AssertionError):
+                _gelu_pins()
+    _gelu_pins()

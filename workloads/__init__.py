@@ -42,6 +42,7 @@ class MoEConfig:
     n_zero: int = 10        # stress: experts that receive nothing
     seed: int = 0
     aux_alpha: float = 0.0  # weight of the auxiliary load-balancing loss (0: not computed)
+    ffn: str = "swiglu"     # expert body: "swiglu" (Wg, Wu, Wd) or "gelu" (two matrices Wg = W^A, Wd = W^B)
 
     @property
     def A(self) -> int:
@@ -52,15 +53,17 @@ class MoEConfig:
         return torch.float32 if self.dtype == "f32" else torch.bfloat16
 
     def flops(self) -> Dict[str, float]:
-        """Algorithmic FLOPs over real rows only (6·d·F per row fwd, 12·d·F bwd)."""
+        """Algorithmic FLOPs over real rows only: per row 6·d·F forward and 12·d·F backward with three
+        matrices per expert, 4·d·F and 8·d·F with two."""
         routed = self.A * self.d * self.d_ff
         shared = self.n_shared * self.T * self.d * self.d_ff_shared
+        m = 3.0 if self.ffn == "swiglu" else 2.0   # matrices per expert
         return {
-            "fwd": 6.0 * (routed + shared),
-            "bwd": 12.0 * (routed + shared),
-            "total": 18.0 * (routed + shared),
-            "routed_total": 18.0 * routed,
-            "shared_total": 18.0 * shared,
+            "fwd": 2.0 * m * (routed + shared),
+            "bwd": 4.0 * m * (routed + shared),
+            "total": 6.0 * m * (routed + shared),
+            "routed_total": 6.0 * m * routed,
+            "shared_total": 6.0 * m * shared,
         }
 
 
@@ -78,6 +81,14 @@ CONFIGS: Dict[str, MoEConfig] = {
     "stress": MoEConfig("stress", T=16384, d=2048, E=60, k=4, d_ff=1408, routing="stress",
                         zipf_s=1.5, aux_alpha=AUX_ALPHA),
 }
+
+# The paper's synthetic models (Table 1): GPT-3 sparsified, two matrices per expert, d_ffn = 4 d_model,
+# top-2, 2 experts per GPU on 32 GPUs = 64 experts; T = four sequences of 2048 tokens on this GPU.
+# The load skew is not given for them: the exponent of the Qwen-shaped workload is reused.
+CONFIGS.update({
+    "gpt-s": MoEConfig("gpt-s", T=8192, d=768, E=64, k=2, d_ff=3072, ffn="gelu", zipf_s=1.0, aux_alpha=AUX_ALPHA),
+    "gpt-l": MoEConfig("gpt-l", T=8192, d=1536, E=64, k=2, d_ff=6144, ffn="gelu", zipf_s=1.0, aux_alpha=AUX_ALPHA),
+})
 
 WEIGHT_STD = 0.02
 TOKEN_STD = 0.02
@@ -181,12 +192,15 @@ def make_weights(cfg: MoEConfig, device: str = "cpu", std: Optional[float] = Non
             w[e].copy_(_normal((rows, cols), std, g, device, cfg.torch_dtype))
         out[name] = w
 
+    gated = cfg.ffn == "swiglu"
     fill("Wg", cfg.E, cfg.d, cfg.d_ff)
-    fill("Wu", cfg.E, cfg.d, cfg.d_ff)
+    if gated:
+        fill("Wu", cfg.E, cfg.d, cfg.d_ff)
     fill("Wd", cfg.E, cfg.d_ff, cfg.d)
     if cfg.n_shared:
         fill("Wsg", cfg.n_shared, cfg.d, cfg.d_ff_shared)
-        fill("Wsu", cfg.n_shared, cfg.d, cfg.d_ff_shared)
+        if gated:
+            fill("Wsu", cfg.n_shared, cfg.d, cfg.d_ff_shared)
         fill("Wsd", cfg.n_shared, cfg.d_ff_shared, cfg.d)
     return out
 
