@@ -50,13 +50,14 @@ def algorithmic_work(cfg: wl.MoEConfig, counts):
     routed = A * d * F
     shared = cfg.n_shared * T * d * cfg.d_ff_shared
     unit = routed + shared
-    flops = {"gemm_fwd_gate_up": 4.0 * unit, "gemm_fwd_down": 2.0 * unit, "gemm_bwd_dh": 2.0 * unit,
-             "gemm_bwd_dx": 4.0 * unit, "gemm_bwd_dwd": 2.0 * unit, "gemm_bwd_dwgu": 4.0 * unit}
+    m_in = 2.0 if cfg.ffn == "swiglu" else 1.0   # matrices on the input side of the expert (Wg, Wu | W^A)
+    flops = {"gemm_fwd_gate_up": 2.0 * m_in * unit, "gemm_fwd_down": 2.0 * unit, "gemm_bwd_dh": 2.0 * unit,
+             "gemm_bwd_dx": 2.0 * m_in * unit, "gemm_bwd_dwd": 2.0 * unit, "gemm_bwd_dwgu": 2.0 * m_in * unit}
     if cfg.dtype == "bf16" and d % 64 == 0 and F % 64 == 0:
         light = int(counts[counts <= LIGHT_GROUP_ROWS].sum()) * d * F
-        flops["gemm_bwd_dw_light"] = 6.0 * light  # two launches: dWd, then dWg and dWu
+        flops["gemm_bwd_dw_light"] = (2.0 + 2.0 * m_in) * light  # two launches: dWd, then dWg (and dWu)
         flops["gemm_bwd_dwd"] -= 2.0 * light
-        flops["gemm_bwd_dwgu"] -= 4.0 * light
+        flops["gemm_bwd_dwgu"] -= 2.0 * m_in * light
     has_sh = 1 if cfg.n_shared else 0
     byts = {
         "route_kernel": T * cfg.E * 4 + T * k * 8,
@@ -102,7 +103,7 @@ def cpu_baseline(cfg, inp, weights, budget_tokens):
     dY = inp["dY"][:n].float().numpy()
     W = {k: LazyExperts(v) for k, v in weights.items()}
     t0 = time.perf_counter()
-    orc.layer_fwd_bwd(lg, X, dY, W["Wg"], W["Wu"], W["Wd"], cfg.k, cfg.gate, cfg.renorm,
+    orc.layer_fwd_bwd(lg, X, dY, W["Wg"], W.get("Wu"), W["Wd"], cfg.k, cfg.gate, cfg.renorm,
                       W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
     dt = time.perf_counter() - t0
     return {"value": n / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
@@ -120,7 +121,7 @@ def verify(cfg, inp, weights, hp):
     worst = 0.0
     for t in (0, cfg.T // 2, cfg.T - 1):
         y, dx, _ = orc.token_fwd_bwd(inp["X"][t].double().numpy(), idx[t], w[t], inp["dY"][t].double().numpy(),
-                                     W["Wg"], W["Wu"], W["Wd"], W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
+                                     W["Wg"], W.get("Wu"), W["Wd"], W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
         for got, ref in ((hp.b["Y"][t], y), (hp.b["dX"][t], dx)):
             err = float(np.abs(got.double().cpu().numpy() - ref).max() / np.abs(ref).max())
             worst = max(worst, err)
@@ -130,7 +131,7 @@ def verify(cfg, inp, weights, hp):
     return worst
 
 
-CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 1024, "phi": 256, "dsv3": 64, "stress": 1024}
+CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 1024, "phi": 256, "dsv3": 64, "stress": 1024, "gpt-s": 2048, "gpt-l": 512}
 
 
 def main():
@@ -165,8 +166,8 @@ def main():
     sh = [weights.get("Wsg"), weights.get("Wsu"), weights.get("Wsd")]
 
     def step():
-        hp.forward(g["logits"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
-        hp.backward(g["dY"], g["X"], weights["Wg"], weights["Wu"], weights["Wd"], *sh)
+        hp.forward(g["logits"], g["X"], weights["Wg"], weights.get("Wu"), weights["Wd"], *sh)
+        hp.backward(g["dY"], g["X"], weights["Wg"], weights.get("Wu"), weights["Wd"], *sh)
 
     for _ in range(max(1, args.warmup)):
         step()

@@ -178,6 +178,12 @@ int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_id
  *   G, U, H   out, [n_rows, d_ff] (shared: [n_groups, n_rows, d_ff]); kept for the backward pass
  *   Yout [n_rows, d]  out
  * shape->d_ff is the width of these experts (shared experts may use their own shape).
+ * Two-matrix experts (Wu == NULL): Eq. 1 as the paper prints it, FFN(x) = f(x W^A) W^B with
+ *   W^A = Wg, W^B = Wd and f = GELU, gelu(z) = z Phi(z) (the paper's synthetic GPT-MoE models;
+ *   it does not name f): G = Xin_e Wg[e] (the pre-activation), H = gelu(G), Yout_e = H Wd[e];
+ *   U is not touched and may be NULL.  In moe_expert_bwd the same mode (Wu == NULL) gives
+ *   dG = (dYin Wd^T) * gelu'(G), gelu'(z) = Phi(z) + z phi(z); dXin = dG Wg^T; dWg = Xin^T dG;
+ *   dWd = H^T dYin; U and dWu_c are not touched and may be NULL.
  */
 int moe_expert_fwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* offsets, int32_t n_rows,
                    const void* Xin, const void* Wg, const void* Wu, const void* Wd, void* G, void* U,

@@ -177,7 +177,16 @@ template <int W> struct Pack<bf16_t, W> {
   }
 };
 
-enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_STORE_F32 = 3, EPI_ADD = 4 };
+enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_STORE_F32 = 3, EPI_ADD = 4, EPI_GELU_FWD = 5,
+       EPI_GELU_BWD = 6 };
+
+// gelu(z) = z Phi(z) and its derivative Phi(z) + z phi(z) (Phi, phi: standard normal distribution
+// function and density); the activation of the two-matrix expert
+__device__ __forceinline__ float normal_cdf(float z) { return 0.5f * (1.f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_f(float z) { return z * normal_cdf(z); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  return normal_cdf(z) + z * 0.3989422804014327f * expf(-0.5f * z * z);
+}
 
 __device__ __forceinline__ uint32_t clip_u32(int64_t v) {
   return v < 0 ? 0u : v > 0xffffffffll ? 0xffffffffu : (uint32_t)v;
@@ -238,6 +247,18 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
 #pragma unroll
       for (int q = 0; q < W; q++) o[q] += v[0][q];
       Pack<T, W>::store((T*)p.out[0] + off, o);
+    } else if (EPI == EPI_GELU_FWD) {    // two-matrix expert: keep the pre-activation, store f of it
+      float h[W];
+#pragma unroll
+      for (int q = 0; q < W; q++) h[q] = gelu_f(v[0][q]);
+      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store((T*)p.out[2] + off, h);
+    } else if (EPI == EPI_GELU_BWD) {    // dZ = dH f'(Z)
+      float z[W], dz[W];
+      Pack<T, W>::load((const T*)p.in[0] + off, z);
+#pragma unroll
+      for (int q = 0; q < W; q++) dz[q] = v[0][q] * gelu_grad_f(z[q]);
+      Pack<T, W>::store((T*)p.out[0] + off, dz);
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[W];
 #pragma unroll
@@ -497,14 +518,15 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(1024), 0, st, a.offsets, a.n_groups, a.n_rows, plan_bm<PATH>(), pl,
                        (int32_t*)nullptr, (int32_t*)nullptr);
   }
-  // F4: dual GEMM with the SwiGLU epilogue
+  // F4: dual GEMM with the SwiGLU epilogue, or (two-matrix expert, Wu == NULL) one GEMM with the GELU epilogue
   RowGemm p = {};
   p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
   p.N = a.F; p.K = a.d; p.n_pairs = 1; p.n_segs = 1;
   p.A[0] = a.Xin; p.lda = a.d; p.a_seg = 0; p.a_rows_out = 0;
   p.B[0] = a.Wg; p.Bdual = a.Wu; p.ldb = a.F; p.b_group = (int64_t)a.d * a.F; p.b_seg = 0;
   p.out[0] = a.G; p.out[1] = a.U; p.out[2] = a.H; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<RowCores<PATH, 2, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
+  if (a.Wu) launch_row<RowCores<PATH, 2, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
+  else launch_row<RowCores<PATH, 1, false>, 1, EPI_GELU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
   // F5: Yout = H Wd (shared mode: summed over groups through K segments)
   RowGemm q = {};
   q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 1;
@@ -553,10 +575,12 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   p.A[0] = a.dYin; p.lda = a.d; p.a_rows_out = 0;
   p.B[0] = a.Wd; p.ldb = a.d; p.b_group = (int64_t)a.F * a.d;
   p.in[0] = a.G; p.in[1] = a.U; p.out[0] = dG; p.out[1] = dU; p.ldc = a.F; p.c_rows_out = 1;
-  launch_row<RowCores<PATH, 1, true>, 1, EPI_SWIGLU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
+  const bool gated = a.Wu != nullptr;  // two-matrix expert otherwise: dG is dZ, no dU
+  if (gated) launch_row<RowCores<PATH, 1, true>, 1, EPI_SWIGLU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
+  else launch_row<RowCores<PATH, 1, true>, 1, EPI_GELU_BWD, true>("gemm_bwd_dh", p, max_tiles, st);
   // B2b: dXin = dG Wg^T + dU Wu^T
   RowGemm q = {};
-  q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = 2;
+  q.n_rows = a.n_rows; q.N = a.d; q.K = a.F; q.n_pairs = gated ? 2 : 1;
   q.A[0] = dG; q.A[1] = dU; q.lda = a.F; q.a_rows_out = 1;
   q.B[0] = a.Wg; q.B[1] = a.Wu; q.ldb = a.F;
   q.out[0] = a.dXin; q.ldc = a.d; q.c_rows_out = 0;
@@ -591,14 +615,16 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       wl_.k_min = vl_.k_min = 1;
       wl_.k_max = vl_.k_max = kLightGroupRows;
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
-      launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
+      if (gated) launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
+      else launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwgu", v, a.n_groups, st);
       launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dw_light", wl_, a.n_groups, st);
-      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dw_light", vl_, a.n_groups, st, 2);
+      launch_w<typename C::template core_light<1>, 1>("gemm_bwd_dw_light", vl_, a.n_groups, st, gated ? 2 : 1);
       return;
     }
   }
   launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
-  launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
+  if (gated) launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
+  else launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwgu", v, a.n_groups, st);
 }
 
 static size_t plan_size_for(int n_groups, int n_rows, bool shared) {
@@ -642,7 +668,7 @@ extern "C" int moe_expert_fwd(const moe_shape_t* shape, int32_t n_groups, const 
   using namespace moe;
   int rc = check_expert_args(shape, n_groups, n_rows, "moe_expert_fwd");
   if (rc) return rc;
-  if (!Wg || !Wu || !Wd || !ws || (n_rows > 0 && (!Xin || !G || !U || !H || !Yout))) {
+  if (!Wg || !Wd || !ws || (n_rows > 0 && (!Xin || !G || (Wu && !U) || !H || !Yout))) {
     set_error("moe_expert_fwd: null pointer");
     return MOE_EINVAL;
   }
@@ -675,8 +701,8 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
   using namespace moe;
   int rc = check_expert_args(shape, n_groups, n_rows, "moe_expert_bwd");
   if (rc) return rc;
-  if (!Wg || !Wu || !Wd || !ws || !active_ids || !n_active || !dWg_c || !dWu_c || !dWd_c ||
-      (n_rows > 0 && (!Xin || !G || !U || !H || !dYin || !dXin))) {
+  if (!Wg || !Wd || !ws || !active_ids || !n_active || !dWg_c || (Wu && !dWu_c) || !dWd_c ||
+      (n_rows > 0 && (!Xin || !G || (Wu && !U) || !H || !dYin || !dXin))) {
     set_error("moe_expert_bwd: null pointer");
     return MOE_EINVAL;
   }

@@ -797,7 +797,10 @@ struct MfmaDmaCore {
             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.w) : "a"(acc[nb][i][j][4 * g + 3]));
             *reinterpret_cast<float4*>(stage + (nb * 32 + (lane & 31)) * RS + j * 32 + 8 * g + 4 * (lane >> 5)) = v;
           }
-#pragma unroll
+      // not unrolled: the epilogue functor may be large (activation functions), and a body that is
+      // too big keeps the compiler from unrolling the loop over i, which would put the accumulators
+      // into scratch memory (their indices must be compile-time constants)
+#pragma unroll 1
       for (int pass = 0; pass < 32 / RPP; pass++) {
         const int row = pass * RPP + lane / LPR, c0 = (lane % LPR) * 8;
         float vals[NB][8];
