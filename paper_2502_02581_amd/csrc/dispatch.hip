@@ -34,18 +34,51 @@ __global__ __launch_bounds__(64) void dispatch_count(const int32_t* __restrict__
   for (int e = lane; e < E; e += 64) hist[(size_t)chunk * E + e] = cnt[e];
 }
 
+// The chunks are cut into C equal runs (C = 1024 / E rounded down to a power of two) so that all 1024
+// threads work: thread (c, e) first sums run c of expert e, the run sums are scanned over c, then
+// the thread rewrites its run as exclusive prefixes.  Loads go eight at a time ahead of the
+// dependent additions and stores.
 __global__ __launch_bounds__(1024) void dispatch_scan(int32_t* __restrict__ hist, int n_chunks, int E,
                                                       int32_t* __restrict__ counts,
                                                       int32_t* __restrict__ offsets) {
   __shared__ int32_t sc[MOE_MAX_EXPERTS];
+  __shared__ int32_t part[1024];
+  int C = 1;
+  while (C * 2 * E <= 1024) C *= 2;
+  const int c = threadIdx.x / E, e_run = threadIdx.x - c * E;
+  const int per = (n_chunks + C - 1) / C;
+  const int w0 = min(n_chunks, c * per), w1 = min(n_chunks, w0 + per);
+  const bool worker = c < C;
+  if (worker) {
+    int sum = 0;
+    for (int w = w0; w < w1; w += 8) {
+      int v[8];
+#pragma unroll
+      for (int q = 0; q < 8; q++) v[q] = w + q < w1 ? hist[(size_t)(w + q) * E + e_run] : 0;
+#pragma unroll
+      for (int q = 0; q < 8; q++) sum += v[q];
+    }
+    part[c * E + e_run] = sum;
+  }
+  __syncthreads();
+  if (worker) {
+    int run = 0;
+    for (int q = 0; q < c; q++) run += part[q * E + e_run];
+    for (int w = w0; w < w1; w += 8) {
+      int v[8];
+#pragma unroll
+      for (int q = 0; q < 8; q++) v[q] = w + q < w1 ? hist[(size_t)(w + q) * E + e_run] : 0;
+#pragma unroll
+      for (int q = 0; q < 8; q++) {
+        if (w + q < w1) hist[(size_t)(w + q) * E + e_run] = run;
+        run += v[q];
+      }
+    }
+  }
   const int e = threadIdx.x;
   int run = 0;
   if (e < E) {
-    for (int c = 0; c < n_chunks; c++) {
-      int v = hist[(size_t)c * E + e];
-      hist[(size_t)c * E + e] = run;
-      run += v;
-    }
+    for (int q = 0; q < C; q++) run += part[q * E + e];
     counts[e] = run;
   }
   sc[e] = e < E ? run : 0;
