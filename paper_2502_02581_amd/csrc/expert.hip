@@ -188,10 +188,6 @@ __device__ __forceinline__ float gelu_grad_f(float z) {
   return normal_cdf(z) + z * 0.3989422804014327f * expf(-0.5f * z * z);
 }
 
-__device__ __forceinline__ uint32_t clip_u32(int64_t v) {
-  return v < 0 ? 0u : v > 0xffffffffll ? 0xffffffffu : (uint32_t)v;
-}
-
 // precise for the fp32 path; hardware exp and reciprocal where the result is rounded to bf16 anyway
 template <typename T> __device__ __forceinline__ float sigmoidf_(float z);
 template <> __device__ __forceinline__ float sigmoidf_<float>(float z) { return 1.f / (1.f + expf(-z)); }

@@ -549,8 +549,10 @@ struct MfmaDmaCore {
   }
 
   template <class SegFn, class Epi>
+  // (the valid extents are not needed here: the descriptors' byte counts zero-fill the loads and the
+  // epilogue functor masks the stores)
   __device__ static __forceinline__ void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb,
-                                             int m_valid, int n_valid, Epi epi) {
+                                             int /*m_valid*/, int /*n_valid*/, Epi epi) {
     const int n_iters = n_segs * nk;
     bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63;

@@ -31,7 +31,7 @@ inline size_t plan_bytes(int n_groups, int max_tiles) {
   return align_up((size_t)max_tiles * sizeof(RowTile), 256) + 256 + align_up((size_t)n_groups * sizeof(int4), 256);
 }
 
-inline Plan carve_plan(void* ws, int n_groups, int max_tiles) {
+inline Plan carve_plan(void* ws, int /*n_groups*/, int max_tiles) {
   char* p = (char*)ws;
   Plan pl;
   pl.tiles = (RowTile*)p;

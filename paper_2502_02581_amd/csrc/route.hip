@@ -233,7 +233,7 @@ __global__ __launch_bounds__(1024) void aux_finish_kernel(const float* __restric
     part[c * E + e] = sum;
   }
   __syncthreads();
-  if (threadIdx.x < E) {
+  if ((int)threadIdx.x < E) {
     float sum = 0.f;
     for (int q = 0; q < C; q++) sum += part[q * E + e];
     const float pe = T > 0 ? sum / (float)T : 0.f;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(1024) void aux_finish_kernel(const float* __restric
 //   sigmoid (p = s / S): dz_e = (c_e - sum_j p_j c_j) / S * s_e (1 - s_e)
 template <int R>
 __global__ __launch_bounds__(256) void aux_bwd_kernel(const float* __restrict__ logits, const int32_t* __restrict__ counts,
-                                                      float* __restrict__ dlogits, int T, int E, int k, int gate,
+                                                      float* __restrict__ dlogits, int T, int E, int gate,
                                                       float scale, int accumulate) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -341,7 +341,7 @@ extern "C" int moe_aux_loss_bwd(const moe_shape_t* shape, const float* logits, c
   dim3 grid((T + 3) / 4), block(256);
   ProfScope prof("aux_loss_bwd", st);
 #define MOE_AUX_BWD(R) \
-  hipLaunchKernelGGL(aux_bwd_kernel<R>, grid, block, 0, st, logits, counts, dlogits, T, E, shape->k, shape->gate, scale, \
+  hipLaunchKernelGGL(aux_bwd_kernel<R>, grid, block, 0, st, logits, counts, dlogits, T, E, shape->gate, scale, \
                      (int)accumulate)
   MOE_BY_EXPERTS(E, MOE_AUX_BWD);
 #undef MOE_AUX_BWD
