@@ -28,7 +28,7 @@ FP32_VEC_PEAK_TF = 157.3
 
 GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx", "gemm_bwd_dwd", "gemm_bwd_dwgu",
                "gemm_bwd_dw_light")
-LIGHT_GROUP_ROWS = 128       # routed experts with at most this many rows take the light weight-gradient kernels
+LIGHT_GROUP_ROWS = 256       # routed experts with at most this many rows take the light weight-gradient kernels
 PROBE_BYTES = 1 << 30        # size of the calibration copy
 PROBE_LAUNCHES = 5
 # kernel behind each profiling label on the bf16 LDS-DMA path, as rocprofv3 names it (one label = one kernel symbol)

@@ -367,7 +367,13 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   extern __shared__ __align__(16) char smem[];
   constexpr int BM = Core::BM, BN = Core::BN, BK = Core::BK;
   const int ntn = (p.N + BN - 1) / BN;
-  const int rank = blockIdx.y, mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
+  // a block computes n_reps consecutive column tiles of one row of tiles (n_reps > 1 only where a
+  // tile is a single short K step: the block's set-up, its group record and the latency of its
+  // first loads are then paid once for several tiles, and the stores of one tile overlap the loads
+  // of the next)
+  const int reps = p.n_reps > 1 ? p.n_reps : 1;
+  const int ntb = (ntn + reps - 1) / reps;
+  const int rank = blockIdx.y, mt = blockIdx.x / ntb, nt_first = (blockIdx.x % ntb) * reps;
   // {group, rows, first row, compact slot}; without records every group has n_rows rows and its own slot
   const int4 gi = p.ginfo ? p.ginfo[rank] : make_int4(rank, p.n_rows, 0, rank);
   // the record is the same for the whole block: keep it in scalar registers, and with it every
@@ -377,10 +383,14 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
   if (K <= 0 || K < p.k_min || K > p.k_max) return;
   // single-product kernels serve the two products of a dual GEMM through blockIdx.z
   const int z = NB == 1 ? blockIdx.z : 0;
-  const int m0 = mt * BM, n0 = nt * BN;
-  const int m_valid = min(BM, p.M - m0), n_valid = min(BN, p.N - n0);
   const int a_row0 = start + (p.a_per_group ? g * p.n_rows : 0);
   const int b_row0 = start + (p.b_per_group ? g * p.n_rows : 0);
+  const int m0 = mt * BM;
+  const int m_valid = min(BM, p.M - m0);
+  for (int nt = nt_first; nt < min(nt_first + reps, ntn); nt++) {
+  const int n0 = nt * BN;
+  const int n_valid = min(BN, p.N - n0);
+  if (nt > nt_first) __syncthreads();  // the previous tile's epilogue is done with LDS in every wave
   auto segf = [&](int) __attribute__((always_inline)) {  // one segment: the rows of the group
     SegSrc<T, NB> s;
     s.a = (const T*)p.A + (int64_t)a_row0 * p.lda + m0;
@@ -406,6 +416,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
 #ifdef MOE_TRACE
   trace_put(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16, t_start);
 #endif
+  }
 }
 
 // ------------------------------------------------------------------------------ host side
@@ -430,7 +441,8 @@ template <> struct Cores<PATH_BF16_DMA> {
   // weight gradients of groups with few rows: 128 x 128 outputs per product, one tile slot
   template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, 0>;
 };
-constexpr int kLightGroupRows = 128;  // groups up to this many rows take the light dW kernel
+constexpr int kLightGroupRows = 256;  // groups up to this many rows take the light dW kernel
+constexpr int kLightReps = 8;         // column tiles per block of that kernel
 
 // The tile cores a row-tiled GEMM launch may use: one for the fp32 and the general bf16 path, four
 // heights (256, 128, 64, 32 rows) for the DMA path so that ragged groups waste little MFMA work.
@@ -484,7 +496,7 @@ static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipSt
 
 template <class Core, int NB>
 static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_t st, int n_products = 1) {
-  const int tiles = ceil_div(p.M, Core::BM) * ceil_div(p.N, Core::BN);
+  const int tiles = ceil_div(p.M, Core::BM) * ceil_div(ceil_div(p.N, Core::BN), p.n_reps > 1 ? p.n_reps : 1);
   if (tiles == 0 || n_groups == 0) return;
   auto kern = w_gemm_kernel<Core, NB>;
   static bool attr_done = false;
@@ -610,6 +622,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       WGemm wl_ = w, vl_ = v;
       wl_.k_min = vl_.k_min = 1;
       wl_.k_max = vl_.k_max = kLightGroupRows;
+      wl_.n_reps = vl_.n_reps = kLightReps;
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
       if (gated) launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
       else launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwgu", v, a.n_groups, st);

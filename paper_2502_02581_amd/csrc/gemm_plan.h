@@ -77,6 +77,7 @@ struct WGemm {
   void* C[2];
   int64_t c_slot;           // elements per slot
   int32_t k_min, k_max;     // only groups with k_min <= rows <= k_max are processed by this launch
+  int32_t n_reps;           // consecutive column tiles per block (0 or 1: one)
 };
 
 }  // namespace moe
