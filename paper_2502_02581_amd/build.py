@@ -5,10 +5,14 @@ import os
 import subprocess
 import sys
 
+from . import asm_check
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
 SOURCES = ["common.hip", "route.hip", "dispatch.hip", "combine.hip", "expert.hip", "planner.hip"]
+# sources with inline-assembly tile loads: their device assembly is kept and checked (asm_check.py)
+CHECKED = ["expert.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -20,6 +24,11 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def device_asm(src: str) -> str:
+    """Where the compile step of `src` leaves its gfx950 assembly."""
+    return os.path.join(HERE, "_build", src.replace(".hip", "") + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+
+
 def build(verbose: bool = True) -> str:
     """Compiles every HIP source and links the shared library; always recompiles."""
     objs = []
@@ -29,6 +38,8 @@ def build(verbose: bool = True) -> str:
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         cmd = [hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src in CHECKED:
+            cmd.insert(1, "-save-temps=obj")
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src, p in procs:
@@ -38,6 +49,10 @@ def build(verbose: bool = True) -> str:
             raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(lines))
         if verbose and any("warning" in ln or "error" in ln for ln in lines):
             print("\n".join(lines), file=sys.stderr)
+    for src in CHECKED:
+        findings = asm_check.check(device_asm(src))
+        if findings:
+            raise RuntimeError(f"device assembly of {src} fails its checks:\n" + "\n".join(findings))
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
