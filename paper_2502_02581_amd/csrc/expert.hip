@@ -141,7 +141,7 @@ template <int W> struct Pack<bf16_t, W> {
   __device__ static __forceinline__ void store(bf16_t* p, const float (&v)[W]) {
     uint32_t w[W / 2];
 #pragma unroll
-    for (int i = 0; i < W / 2; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    for (int i = 0; i < W / 2; i++) w[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
     if (W == 4) *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
     else *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[W / 2 - 2], w[W / 2 - 1]);
   }
@@ -151,7 +151,7 @@ template <int W> struct Pack<bf16_t, W> {
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
     uint32_t w[W / 2];
 #pragma unroll
-    for (int i = 0; i < W / 2; i++) w[i] = (uint32_t)f32_to_bf16(v[2 * i]) | ((uint32_t)f32_to_bf16(v[2 * i + 1]) << 16);
+    for (int i = 0; i < W / 2; i++) w[i] = f32x2_to_bf16x2(v[2 * i], v[2 * i + 1]);
     if (W == 4) {
       u32x2 t = {w[0], w[1]};
       __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));

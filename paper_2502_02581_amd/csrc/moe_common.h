@@ -40,12 +40,21 @@ typedef uint16_t bf16_t;  // storage type; arithmetic is always fp32
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 
-// round to nearest even (NaN stays NaN)
+// Round to nearest even (NaN stays NaN) with the conversion instruction of gfx950
+// (v_cvt_pk_bf16_f32: two values per instruction).  Written out with integer arithmetic and a NaN
+// test, the same conversion costs a dozen instructions and a divergent branch per value, which made
+// the GEMM epilogues several times slower than their stores.
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+  const __bf16 r = (__bf16)f;
+  return __builtin_bit_cast(bf16_t, r);
+}
+// two values in one register: `lo` in bits 0..15
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_hw_t;
+  typedef __attribute__((ext_vector_type(2))) float f32x2_hw_t;
+  const f32x2_hw_t v = {lo, hi};
+  const bf16x2_hw_t r = __builtin_convertvector(v, bf16x2_hw_t);
+  return __builtin_bit_cast(uint32_t, r);
 }
 
 template <typename T> struct Elem;
@@ -87,7 +96,7 @@ template <> struct Vec16<bf16_t> {
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; i++)
-      w[i] = (uint32_t)f32_to_bf16(o[2 * i]) | ((uint32_t)f32_to_bf16(o[2 * i + 1]) << 16);
+      w[i] = f32x2_to_bf16x2(o[2 * i], o[2 * i + 1]);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 };
