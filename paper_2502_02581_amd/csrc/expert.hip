@@ -124,6 +124,7 @@ __global__ __launch_bounds__(1024) void plan_kernel(const int32_t* __restrict__ 
 // W consecutive elements (W = 4 or 8) narrowed from / widened to fp32, one or two 16-byte accesses
 template <typename T, int W> struct Pack;
 template <int W> struct Pack<float, W> {
+  __device__ static __forceinline__ void widen(const uint4&, float (&)[W]) {}  // (bf16 only)
   __device__ static __forceinline__ void store(float* p, const float (&v)[W]) {
 #pragma unroll
     for (int i = 0; i < W; i += 4) *reinterpret_cast<float4*>(p + i) = make_float4(v[i], v[i + 1], v[i + 2], v[i + 3]);
@@ -158,6 +159,17 @@ template <int W> struct Pack<bf16_t, W> {
     } else {
       u32x4 t = {w[0], w[1], w[W / 2 - 2], w[W / 2 - 1]};
       __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+    }
+  }
+  // the same from a 16-byte piece that is already in registers (W == 8)
+  __device__ static __forceinline__ void widen(const uint4& t, float (&v)[W]) {
+    if constexpr (W == 8) {  // (cores that hand over four values at a time do their own loads)
+      const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        v[2 * i] = __uint_as_float(w[i] << 16);
+        v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
     }
   }
   __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[W]) {
@@ -195,6 +207,22 @@ template <> __device__ __forceinline__ float sigmoidf_<bf16_t>(float z) {
   return __builtin_amdgcn_rcpf(1.f + __expf(-z));
 }
 
+// An epilogue whose global reads the LDS-DMA core may request ahead of time (see EpiAux): `body` does
+// the work, with the pieces `pre` has fetched or, handed a null pointer, with loads of its own.
+template <class Body, class Pre, class Aux, int N_AUX>
+struct EpiWithAux {
+  static constexpr int kAux = N_AUX;
+  Body body;
+  Pre pre;
+  __device__ __forceinline__ Aux prefetch(int m, int n) const { return pre(m, n); }
+  template <class V> __device__ __forceinline__ void operator()(int m, int n, const V& v) const {
+    body(m, n, v, (const Aux*)nullptr);
+  }
+  template <class V> __device__ __forceinline__ void operator()(int m, int n, const V& v, const Aux& a) const {
+    body(m, n, v, &a);
+  }
+};
+
 // --------------------------------------------------------------------- row-tiled GEMM kernel
 // CoreSet::tile<KIND> is the tile core of a tile kind; kinds differ in height only (same BN, BK), so
 // one launch serves full tiles and the short tiles of ragged groups.
@@ -229,7 +257,23 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   };
   const int c_row0 = p.c_rows_out ? t.row0_out : t.row0_in;
   // W consecutive columns of one row (W = 4 from the fp32 and general cores, 8 from the DMA core)
-  auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) {
+  // 16-byte pieces the epilogue reads at its own position, requested ahead of time by the LDS-DMA
+  // core (bf16): the saved inputs of the activation's derivative, or the output to accumulate into
+  constexpr int kAuxLoads = sizeof(T) != 2 ? 0 : EPI == EPI_SWIGLU_BWD ? 2 : (EPI == EPI_GELU_BWD || EPI == EPI_ADD) ? 1 : 0;
+  struct Aux {
+    uint4 r[kAuxLoads > 0 ? kAuxLoads : 1];
+  };
+  auto pre = [&](int m, int n) __attribute__((always_inline)) {
+    Aux a;
+    // out of range: the first piece of the tile, which exists and is never used
+    const bool ok = m < rows && n < n_valid;
+    const int64_t off = (int64_t)(c_row0 + (ok ? m : 0)) * p.ldc + n0 + (ok ? n : 0);
+    const void* src0 = EPI == EPI_ADD ? (const void*)p.out[0] : p.in[0];
+    a.r[0] = *reinterpret_cast<const uint4*>((const T*)src0 + off);
+    if (kAuxLoads == 2) a.r[kAuxLoads > 1 ? 1 : 0] = *reinterpret_cast<const uint4*>((const T*)p.in[1] + off);
+    return a;
+  };
+  auto body = [&](int m, int n, const auto& v, const Aux* aux) __attribute__((always_inline)) {
     constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= rows || n >= n_valid) return;
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
@@ -239,7 +283,8 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       Pack<float, W>::store((float*)p.out[0] + off, v[0]);
     } else if (EPI == EPI_ADD) {        // accumulate into the output
       float o[W];
-      Pack<T, W>::load((const T*)p.out[0] + off, o);
+      if (aux) Pack<T, W>::widen(aux->r[0], o);
+      else Pack<T, W>::load((const T*)p.out[0] + off, o);
 #pragma unroll
       for (int q = 0; q < W; q++) o[q] += v[0][q];
       Pack<T, W>::store((T*)p.out[0] + off, o);
@@ -251,7 +296,8 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       Pack<T, W>::store((T*)p.out[2] + off, h);
     } else if (EPI == EPI_GELU_BWD) {    // dZ = dH f'(Z)
       float z[W], dz[W];
-      Pack<T, W>::load((const T*)p.in[0] + off, z);
+      if (aux) Pack<T, W>::widen(aux->r[0], z);
+      else Pack<T, W>::load((const T*)p.in[0] + off, z);
 #pragma unroll
       for (int q = 0; q < W; q++) dz[q] = v[0][q] * gelu_grad_f(z[q]);
       Pack<T, W>::store((T*)p.out[0] + off, dz);
@@ -264,8 +310,13 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       Pack<T, W>::store((T*)p.out[2] + off, h);
     } else {
       float g[W], u[W], dg[W], du[W];
-      Pack<T, W>::load((const T*)p.in[0] + off, g);
-      Pack<T, W>::load((const T*)p.in[1] + off, u);
+      if (aux) {
+        Pack<T, W>::widen(aux->r[0], g);
+        Pack<T, W>::widen(aux->r[kAuxLoads > 1 ? 1 : 0], u);
+      } else {
+        Pack<T, W>::load((const T*)p.in[0] + off, g);
+        Pack<T, W>::load((const T*)p.in[1] + off, u);
+      }
 #pragma unroll
       for (int q = 0; q < W; q++) {
         const float s = sigmoidf_<T>(g[q]);
@@ -276,7 +327,13 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       Pack<T, W>::store((T*)p.out[1] + off, du);
     }
   };
-  Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
+  if constexpr (kAuxLoads > 0) {
+    EpiWithAux<decltype(body), decltype(pre), Aux, kAuxLoads> epi{body, pre};
+    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
+  } else {
+    auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) { body(m, n, v, (const Aux*)nullptr); };
+    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
+  }
 }
 
 #ifdef MOE_TRACE

@@ -13,6 +13,14 @@
 
 namespace moe {
 
+// An epilogue functor may read global memory at the position it writes (an activation's saved input,
+// an output it accumulates into).  If it says how many 16-byte pieces per position (`kAux`) and offers
+// `prefetch(m, n)` returning them, the LDS-DMA core requests the pieces of a whole block of rows
+// before it needs them and hands each back through a fourth argument; otherwise the functor does
+// its own loads, one position after the other.
+template <class E, class = void> struct EpiAux { static constexpr int value = 0; };
+template <class E> struct EpiAux<E, std::void_t<decltype(E::kAux)>> { static constexpr int value = E::kAux; };
+
 // Start of one segment.  Pointers are already offset to the tile's first row/column at k = 0;
 // "kc" (K-contiguous) operands are [rows][K] row-major, otherwise [K][rows] row-major.
 template <typename T, int NB>
@@ -784,8 +792,9 @@ struct MfmaDmaCore {
     static_assert(NW * NB * 32 * RS * 4 <= LDS_BYTES, "staging regions of the waves fit into LDS");
     static_assert(NW * NB * 32 * RS * 4 == STAGING_BYTES, "STAGING_BYTES matches the staging layout");
     float* stage = reinterpret_cast<float*>(smem) + wave * (NB * 32 * RS);
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
+    constexpr int kAux = EpiAux<Epi>::value;
+    constexpr int NPASS = 32 / RPP;
+    auto stage_block = [&](int i) __attribute__((always_inline)) {
 #pragma unroll
       for (int nb = 0; nb < NB; nb++)
 #pragma unroll
@@ -799,21 +808,53 @@ struct MfmaDmaCore {
             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v.w) : "a"(acc[nb][i][j][4 * g + 3]));
             *reinterpret_cast<float4*>(stage + (nb * 32 + (lane & 31)) * RS + j * 32 + 8 * g + 4 * (lane >> 5)) = v;
           }
-      // not unrolled: the epilogue functor may be large (activation functions), and a body that is
-      // too big keeps the compiler from unrolling the loop over i, which would put the accumulators
-      // into scratch memory (their indices must be compile-time constants)
-#pragma unroll 1
-      for (int pass = 0; pass < 32 / RPP; pass++) {
-        const int row = pass * RPP + lane / LPR, c0 = (lane % LPR) * 8;
-        float vals[NB][8];
+    };
+    auto read_pass = [&](int pass, float (&vals)[NB][8]) __attribute__((always_inline)) {
+      const int row = pass * RPP + lane / LPR, c0 = (lane % LPR) * 8;
 #pragma unroll
-        for (int nb = 0; nb < NB; nb++) {
-          const float4 lo = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0);
-          const float4 hi = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0 + 4);
-          vals[nb][0] = lo.x; vals[nb][1] = lo.y; vals[nb][2] = lo.z; vals[nb][3] = lo.w;
-          vals[nb][4] = hi.x; vals[nb][5] = hi.y; vals[nb][6] = hi.z; vals[nb][7] = hi.w;
+      for (int nb = 0; nb < NB; nb++) {
+        const float4 lo = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0);
+        const float4 hi = *reinterpret_cast<const float4*>(stage + (nb * 32 + row) * RS + c0 + 4);
+        vals[nb][0] = lo.x; vals[nb][1] = lo.y; vals[nb][2] = lo.z; vals[nb][3] = lo.w;
+        vals[nb][4] = hi.x; vals[nb][5] = hi.y; vals[nb][6] = hi.z; vals[nb][7] = hi.w;
+      }
+    };
+    const int c0 = (lane % LPR) * 8;
+    if constexpr (kAux > 0) {
+      // the functor's own global reads of block i + 1 are in flight while block i is staged,
+      // converted and stored (everything unrolled: the pieces live in registers)
+      typedef decltype(epi.prefetch(0, 0)) Aux;
+      Aux aux[2][NPASS];
+#pragma unroll
+      for (int pass = 0; pass < NPASS; pass++) aux[0][pass] = epi.prefetch(wm0 + pass * RPP + lane / LPR, wn0 + c0);
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        stage_block(i);
+        if (i + 1 < TM) {
+#pragma unroll
+          for (int pass = 0; pass < NPASS; pass++)
+            aux[(i + 1) & 1][pass] = epi.prefetch(wm0 + (i + 1) * 32 + pass * RPP + lane / LPR, wn0 + c0);
         }
-        epi(wm0 + i * 32 + row, wn0 + c0, vals);
+#pragma unroll
+        for (int pass = 0; pass < NPASS; pass++) {
+          float vals[NB][8];
+          read_pass(pass, vals);
+          epi(wm0 + i * 32 + pass * RPP + lane / LPR, wn0 + c0, vals, aux[i & 1][pass]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        stage_block(i);
+        // not unrolled: the epilogue functor may be large (activation functions), and a body that is
+        // too big keeps the compiler from unrolling the loop over i, which would put the accumulators
+        // into scratch memory (their indices must be compile-time constants)
+#pragma unroll 1
+        for (int pass = 0; pass < NPASS; pass++) {
+          float vals[NB][8];
+          read_pass(pass, vals);
+          epi(wm0 + i * 32 + pass * RPP + lane / LPR, wn0 + c0, vals);
+        }
       }
     }
   }
