@@ -193,11 +193,31 @@ enum { EPI_STORE = 0, EPI_SWIGLU_FWD = 1, EPI_SWIGLU_BWD = 2, EPI_STORE_F32 = 3,
        EPI_GELU_BWD = 6 };
 
 // gelu(z) = z Phi(z) and its derivative Phi(z) + z phi(z) (Phi, phi: standard normal distribution
-// function and density); the activation of the two-matrix expert
-__device__ __forceinline__ float normal_cdf(float z) { return 0.5f * (1.f + erff(z * 0.70710678118654752f)); }
-__device__ __forceinline__ float gelu_f(float z) { return z * normal_cdf(z); }
-__device__ __forceinline__ float gelu_grad_f(float z) {
-  return normal_cdf(z) + z * 0.3989422804014327f * expf(-0.5f * z * z);
+// function and density); the activation of the two-matrix expert.  `e` receives exp(-z^2 / 2).
+// fp32 path: the library's erf and exp.  bf16 path (the result is rounded to bf16 anyway): the
+// rational-times-exponential approximation of erf (Abramowitz & Stegun 7.1.26, absolute error below
+// 1.5e-7) on the hardware's exp and reciprocal, a quarter of the instructions.
+template <typename T> __device__ __forceinline__ float normal_cdf_(float z, float& e);
+template <> __device__ __forceinline__ float normal_cdf_<float>(float z, float& e) {
+  e = expf(-0.5f * z * z);
+  return 0.5f * (1.f + erff(z * 0.70710678118654752f));
+}
+template <> __device__ __forceinline__ float normal_cdf_<bf16_t>(float z, float& e) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(1.f + 0.3275911f * x);
+  e = __expf(-x * x);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float half_erfc = 0.5f * poly * e;  // (1 - erf(x)) / 2
+  return z < 0.f ? half_erfc : 1.f - half_erfc;
+}
+template <typename T> __device__ __forceinline__ float gelu_f(float z) {
+  float e;
+  return z * normal_cdf_<T>(z, e);
+}
+template <typename T> __device__ __forceinline__ float gelu_grad_f(float z) {
+  float e;
+  const float cdf = normal_cdf_<T>(z, e);
+  return cdf + z * 0.3989422804014327f * e;
 }
 
 // precise for the fp32 path; hardware exp and reciprocal where the result is rounded to bf16 anyway
@@ -291,7 +311,7 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
     } else if (EPI == EPI_GELU_FWD) {    // two-matrix expert: keep the pre-activation, store f of it
       float h[W];
 #pragma unroll
-      for (int q = 0; q < W; q++) h[q] = gelu_f(v[0][q]);
+      for (int q = 0; q < W; q++) h[q] = gelu_f<T>(v[0][q]);
       Pack<T, W>::store((T*)p.out[0] + off, v[0]);
       Pack<T, W>::store((T*)p.out[2] + off, h);
     } else if (EPI == EPI_GELU_BWD) {    // dZ = dH f'(Z)
@@ -299,7 +319,7 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       if (aux) Pack<T, W>::widen(aux->r[0], z);
       else Pack<T, W>::load((const T*)p.in[0] + off, z);
 #pragma unroll
-      for (int q = 0; q < W; q++) dz[q] = v[0][q] * gelu_grad_f(z[q]);
+      for (int q = 0; q < W; q++) dz[q] = v[0][q] * gelu_grad_f<T>(z[q]);
       Pack<T, W>::store((T*)p.out[0] + off, dz);
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[W];
