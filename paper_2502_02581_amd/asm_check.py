@@ -8,7 +8,9 @@ not look into.  Two things it would otherwise guarantee are therefore checked on
     the five wait states before the load (the M0 write in front of the load is a scalar instruction
     and has its own wait state inside the inline assembly);
   * no GEMM kernel keeps anything in scratch memory: accumulator tiles that end up there (an
-    epilogue too large to unroll did that once) cost a factor of four and show up nowhere else.
+    epilogue too large to unroll did that once) cost a factor of four and show up nowhere else;
+  * no packed fp32 arithmetic (v_pk_add_f32, v_pk_mul_f32, v_pk_fma_f32): the build switches the
+    feature off (`-packed-fp32-ops`), and this makes sure the switch is still in the flags.
 
 `check(path)` returns a list of findings (empty: fine); `python -m paper_2502_02581_amd.asm_check file.s`
 prints them.
@@ -91,10 +93,20 @@ def check_no_scratch(lines: List[str], name_part: str = "gemm_kernel") -> List[s
     return findings
 
 
+def check_no_packed_fp32(lines: List[str]) -> List[str]:
+    findings = []
+    for ln, t in _instructions(lines):
+        if t.startswith(("v_pk_add_f32", "v_pk_mul_f32", "v_pk_fma_f32")):
+            findings.append(f"line {ln}: packed fp32 instruction `{t}`")
+            if len(findings) >= 5:
+                break
+    return findings
+
+
 def check(path: str) -> List[str]:
     with open(path) as f:
         lines = f.read().split("\n")
-    return check_descriptor_hazards(lines) + check_no_scratch(lines)
+    return check_descriptor_hazards(lines) + check_no_scratch(lines) + check_no_packed_fp32(lines)
 
 
 if __name__ == "__main__":

@@ -43,6 +43,11 @@ def test_scratch_in_a_gemm_kernel_is_flagged():
     assert len(found) == 1 and "row_gemm_kernel" in found[0] and "1088" in found[0]
 
 
+def test_packed_fp32_is_flagged():
+    assert asm_check.check_no_packed_fp32(_asm("\tv_pk_fma_f32 v[0:1], v[2:3], v[4:5], v[6:7]"))
+    assert asm_check.check_no_packed_fp32(_asm("\tv_fma_f32 v0, v1, v2, v3", "\tv_pk_add_f16 v0, v1, v2")) == []
+
+
 def test_current_build_passes():
     for src in build.CHECKED:
         path = build.device_asm(src)
