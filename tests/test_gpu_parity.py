@@ -196,6 +196,56 @@ def test_route_ties_and_masks():
             np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=1e-5, atol=1e-30)
 
 
+def _bf16_nearest_even(x32: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns of fp32 values, from the definition: the nearer of the two neighbouring
+    bfloat16 values (exact comparison in fp64), the one with an even last bit on a tie."""
+    u = x32.view(np.uint32).astype(np.uint64)
+    lo = u & 0xFFFF0000                       # towards zero
+    hi = lo + 0x10000                         # away from zero (may carry into the exponent: that is the next value)
+    f = lambda b: b.astype(np.uint32).view(np.float32).astype(np.float64)
+    x = x32.astype(np.float64)
+    with np.errstate(invalid="ignore", over="ignore"):
+        d_lo, d_hi = np.abs(x - f(lo)), np.abs(f(hi) - x)
+        # past the largest finite bfloat16 the upper neighbour is infinity, whose distance is measured
+        # to the value the format would have there (2^128)
+        top = (lo & 0x7FFF0000) == 0x7F7F0000
+        d_hi = np.where(top, np.abs(np.ldexp(1.0, 128) - np.abs(x)), d_hi)
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & ((lo >> 16) & 1 == 1))
+    out = np.where(take_hi, hi, lo) >> 16
+    return out.astype(np.uint16)
+
+
+def test_bf16_rounding_is_nearest_even():
+    """The bf16 outputs are rounded by the conversion instruction of the chip; pin its rounding, bit for
+    bit, through the combine kernel: one token per value, top-1, a row of ones, weight = the value."""
+    import paper_2502_02581_amd as moe
+
+    rng = np.random.default_rng(11)
+    # (no -0.0: the kernel adds the product to a sum that starts at +0)
+    special = np.array([0.0, 1.0, -1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20,
+                        1.0 + 2.0 ** -7, 1.0 - 2.0 ** -9, 3.3895314e38, 3.3961775e38, 3.4e38, -3.4e38, np.inf, -np.inf,
+                        1e-38, 1.1754944e-38, 5.877e-39, 1e-40, 9.18e-41, 4.6e-41, 1e-45, 65504.0, 0.1, -0.3, 1 / 3],
+                       dtype=np.float32)
+    bits = rng.integers(0, 2 ** 32, size=4096 - len(special), dtype=np.uint64).astype(np.uint32)
+    vals = np.concatenate([special, bits.view(np.float32)])
+    vals = vals[~np.isnan(vals)]
+    T = len(vals)
+    shape = moe.MoEShape(T, 8, 4, 1, 8, "bf16")
+    Yp = torch.ones(T, 8, dtype=torch.bfloat16, device="cuda")
+    row_of = torch.arange(T, dtype=torch.int32, device="cuda").reshape(T, 1)
+    w = torch.from_numpy(vals.copy()).reshape(T, 1).cuda()
+    Y = torch.zeros(T, 8, dtype=torch.bfloat16, device="cuda")
+    moe.moe_combine(shape, Yp, row_of, w, None, Y)
+    got = Y.cpu().view(torch.int16).numpy().view(np.uint16)
+    want = _bf16_nearest_even(vals)
+    assert np.array_equal(got, np.repeat(want[:, None], 8, axis=1)), \
+        [(float(v), hex(int(g)), hex(int(e))) for v, g, e in zip(vals, got[:, 0], want) if g != e][:8]
+    # NaN stays NaN
+    wn = torch.full((T, 1), float("nan"), device="cuda")
+    moe.moe_combine(shape, Yp, row_of, wn, None, Y)
+    assert bool(torch.isnan(Y.float()).all())
+
+
 @pytest.mark.parametrize("E,k", [(1, 1), (8, 8), (64, 3), (65, 2), (256, 8), (300, 6), (1024, 64)])
 def test_route_dispatch_shapes(E, k):
     import paper_2502_02581_amd as moe
