@@ -568,24 +568,28 @@ struct MfmaDmaCore {
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
 
     f32x16_t acc[NB][TM][TN];
+    // Called once the first tile loads are on their way, so that the 16 * NB * TM * TN register
+    // writes overlap their latency.
+    auto zero_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++)
+      for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-      for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++)
+          for (int j = 0; j < TN; j++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) acc[nb][i][j][r] = 0.f;
-    // Pin the zeroing here.  Left alone, the compiler may materialise an accumulator's zeros right
-    // in front of its first MFMA; that MFMA is inline assembly, so nobody would insert the wait
-    // states a VALU write to an accumulator register needs before an MFMA reads it.
+            for (int r = 0; r < 16; r++) acc[nb][i][j][r] = 0.f;
+      // Pin the zeroing here.  Left alone, the compiler may materialise an accumulator's zeros right
+      // in front of its first MFMA; that MFMA is inline assembly, so nobody would insert the wait
+      // states a VALU write to an accumulator register needs before an MFMA reads it.
 #pragma unroll
-    for (int nb = 0; nb < NB; nb++)
+      for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-      for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
-    asm volatile("s_nop 7" ::: "memory");
+          for (int j = 0; j < TN; j++) asm volatile("" : "+a"(acc[nb][i][j])::"memory");
+      asm volatile("s_nop 7" ::: "memory");
+    };
 
     // per-lane byte offsets of this wave's loads of a tile, fixed for the whole K loop
     uint32_t voa[A_NI], vob[B_NI];
@@ -634,6 +638,7 @@ struct MfmaDmaCore {
       if (n_iters > 0) {
         for (int it = 0; it < DEPTH; it++) issue_tile(it);
       }
+      zero_acc();
       for (int it = 0; it < n_iters; it++) {
         // tile `it` has landed once at most the DEPTH - 1 younger tiles are outstanding (loads
         // complete in order); the barrier also says that every wave is done with tile it - 1,
@@ -657,6 +662,7 @@ struct MfmaDmaCore {
       // single slot: load a tile, wait, multiply; k-steps beyond the rows of K are skipped
       Cursor s0;
       start(s0);
+      zero_acc();
       for (int it = 0; it < n_iters; it++) {
         if (it > 0) __syncthreads();
 #pragma unroll
@@ -691,6 +697,7 @@ struct MfmaDmaCore {
       for (int j = 0; j < A_NI; j++) load_a(s2, 1, j);
       step(s2);
     }
+    zero_acc();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
