@@ -31,6 +31,7 @@ GEMM_LABELS = ("gemm_fwd_gate_up", "gemm_fwd_down", "gemm_bwd_dh", "gemm_bwd_dx"
 LIGHT_GROUP_ROWS = 256       # routed experts with at most this many rows take the light weight-gradient kernels
 PROBE_BYTES = 1 << 30        # size of the calibration copy
 PROBE_LAUNCHES = 5
+COLD_STEPS = 3               # steps of the cold-cache variant
 # kernel behind each profiling label on the bf16 LDS-DMA path, as rocprofv3 names it (one label = one kernel symbol)
 SYMBOL = {
     "gemm_fwd_gate_up": "moe::row_gemm_kernel<moe::RowCores<2, 2, false>, 2, 1, false>(moe::RowGemm)",
@@ -188,6 +189,16 @@ def main():
     torch.cuda.synchronize()
     prof = moe.moe_profile_report()
     moe.moe_profile_enable(False)
+    # cold-cache variant (outside the timed region, reported beside `value`): L2 and the infinity cache are
+    # overwritten before every step by filling the 2 GiB probe buffer, and each step is timed on its own
+    cold = []
+    for _ in range(COLD_STEPS):
+        probe.fill_(2)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        cold.append(time.perf_counter() - t1)
     del probe
     probe_ms = prof.pop("copy_probe_kernel")[1] / PROBE_LAUNCHES
 
@@ -229,6 +240,7 @@ def main():
                    "load_share_std": round(float((counts.double() / counts.sum()).std(unbiased=False)), 5)},
         "grouped_gemm_tflops": round(gemm_tflops, 2), "grouped_gemm_frac_mfma_peak": round(gemm_tflops / peak, 4),
         "total_tflops": round(cfg.flops()["total"] / (ms_per_step * 1e-3) / 1e12, 2),
+        "cold_cache_ms_per_step": round(sum(cold) / len(cold) * 1e3, 4),
         "roofline": roofline, "kernels": kernels,
         "copy_probe": {"bytes_each_way": PROBE_BYTES, "ms": round(probe_ms, 4),
                        "gbs": round(2 * PROBE_BYTES / (probe_ms * 1e-3) / 1e9, 1)}, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
