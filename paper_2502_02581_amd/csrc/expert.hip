@@ -358,11 +358,13 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
 
 #ifdef MOE_TRACE
 // Development aid (compiled in only with -DMOE_TRACE): one record per tile of the GEMM kernels,
-// {block, kernel id, group, column tile | kind << 8 | rows << 16, start, end}, times from the
-// 100 MHz wall clock; read back through moe_trace_read.
+// {block, kernel id, group, column tile | kind << 8 | rows << 16, start, end, phase cycles}, times
+// from the 100 MHz wall clock, phases (set-up and first loads, K loop, epilogue, rest) in shader
+// clock cycles; read back through moe_trace_read.
 struct TraceRec {
   int32_t block, kernel, group, what;
   unsigned long long t0, t1;
+  int32_t ph[4];
 };
 constexpr int kTraceMax = 1 << 18;
 __device__ TraceRec g_trace[kTraceMax];
@@ -372,7 +374,11 @@ __device__ __forceinline__ void trace_put(int kernel, int group, int what, unsig
   if (threadIdx.x == 0) {
     const int i = atomicAdd(&g_trace_n, 1);
     if (i < kTraceMax) {
-      TraceRec r = {(int32_t)(blockIdx.x + blockIdx.y * gridDim.x), kernel, group, what, t0, (unsigned long long)wall_clock64()};
+      TraceRec r = {(int32_t)(blockIdx.x + blockIdx.y * gridDim.x), kernel, group, what, t0, (unsigned long long)wall_clock64(), {0, 0, 0, 0}};
+      const long long* ph = g_ph + (blockIdx.x & 0xffff) * 4;
+      const long long now = clock64();
+      r.ph[0] = (int32_t)(ph[1] - ph[0]); r.ph[1] = (int32_t)(ph[2] - ph[1]); r.ph[2] = (int32_t)(ph[3] - ph[2]);
+      r.ph[3] = (int32_t)(now - ph[3]);
       g_trace[i] = r;
     }
   }

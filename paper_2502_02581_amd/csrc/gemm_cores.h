@@ -12,6 +12,15 @@
 #include "moe_common.h"
 
 namespace moe {
+// Development aid (compiled in only with -DMOE_TRACE): the LDS-DMA core stamps the shader clock where
+// a tile's phases end -- 0: entry, 1: first operand tiles in LDS (ring pipeline only), 2: K loop
+// done, 3: epilogue done (first wavefront) -- and the kernels' trace records carry the differences.
+#ifdef MOE_TRACE
+__device__ long long g_ph[65536 * 4];
+#define MOE_PHASE(i) do { if (threadIdx.x == 0) g_ph[(blockIdx.x & 0xffff) * 4 + (i)] = clock64(); } while (0)
+#else
+#define MOE_PHASE(i) do {} while (0)
+#endif
 
 // An epilogue functor may read global memory at the position it writes (an activation's saved input,
 // an output it accumulates into).  If it says how many 16-byte pieces per position (`kAux`) and offers
@@ -562,6 +571,7 @@ struct MfmaDmaCore {
   __device__ static __forceinline__ void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb,
                                              int /*m_valid*/, int /*n_valid*/, Epi epi) {
     const int n_iters = n_segs * nk;
+    MOE_PHASE(0);
     bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -700,6 +710,7 @@ struct MfmaDmaCore {
     zero_acc();
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    MOE_PHASE(1);
 
     // A wave issues in order and a tile load holds it for as long as the memory pipeline has no
     // free slot, so the overlap of loads, LDS reads and MFMAs is written into the instruction
@@ -768,6 +779,7 @@ struct MfmaDmaCore {
     }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // zero-length loads of the tail
+    MOE_PHASE(2);
     // The accumulators live in AGPRs.  Each value is copied out right where it is needed (the
     // volatile asm pins the order); left to itself the compiler copies all 256 at the loop exit,
     // needs every arch VGPR for that and spills the loop's address registers.
@@ -864,6 +876,7 @@ struct MfmaDmaCore {
         }
       }
     }
+    MOE_PHASE(3);
   }
 };
 
