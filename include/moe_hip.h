@@ -166,6 +166,24 @@ int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_id
                  size_t ws_bytes, void* stream);
 
 /*
+ * moe_dispatch_static -- moe_dispatch for callers that cannot allocate device memory or cannot hand over
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels and same results as moe_dispatch, without `ws`: the per-chunk
+ * histograms live in an array that is part of the library's code object (4 * MOE_DISPATCH_STATIC_MAX_COUNTERS
+ * bytes = 1 MiB on every GPU the library runs on, until the process ends).  The call allocates
+ * nothing and frees nothing (with per-kernel timing off: moe_profile_enable creates events).
+ *   limit: ceil(T*k / 256) * E <= MOE_DISPATCH_STATIC_MAX_COUNTERS, else MOE_EWS and nothing is launched
+ *   (T*k = 65536 assignments over 1024 experts, or 2^20 assignments over 64 experts, fit).
+ * Every call on one GPU uses that GPU's one array: two calls that overlap in time on the same GPU
+ * (different streams) race; calls on one stream are ordered and need no clearing in between (every
+ * counter a call reads was written by the same call).  The array's address is looked up once per
+ * device on the first call with that device current; a failure there returns MOE_ELAUNCH.
+ */
+#define MOE_DISPATCH_STATIC_MAX_COUNTERS 262144
+int moe_dispatch_static(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                        int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* stream);
+
+/*
  * moe_expert_fwd -- the expert bodies of Eq. 3 as a grouped GEMM over variable row counts.
  * Grouped mode (offsets != NULL): group e owns rows [offsets[e], offsets[e+1]) of Xin;
  *   G = Xin_e Wg[e], U = Xin_e Wu[e], H = silu(G) * U, Yout_e = H Wd[e].

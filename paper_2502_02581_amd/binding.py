@@ -19,7 +19,8 @@ EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd
            "moe_expert_bwd_workspace_bytes", "moe_route", "moe_dispatch", "moe_expert_fwd", "moe_expert_bwd",
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
            "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd",
-           "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch"]
+           "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch",
+           "moe_dispatch_static"]
 
 
 class MoEError(RuntimeError):
@@ -101,6 +102,8 @@ def load_library():
     lib.moe_route_bwd.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.moe_dispatch.restype = ctypes.c_int
     lib.moe_dispatch.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_dispatch_static.restype = ctypes.c_int
+    lib.moe_dispatch_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_expert_fwd.restype = ctypes.c_int
     lib.moe_expert_fwd.argtypes = [shp, i32, vp, i32] + [vp] * 9 + [sz, vp]
     lib.moe_expert_bwd.restype = ctypes.c_int
@@ -285,6 +288,16 @@ def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, 
                                      _ptr(Xp, dt, "Xp"), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(),
                                      _stream(stream))
     _check(rc, "moe_dispatch")
+
+
+def moe_dispatch_static(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, stream=None):
+    """moe_dispatch without a workspace argument (the library's built-in scratch array; allocates nothing)."""
+    dt = shape.torch_dtype
+    rc = load_library().moe_dispatch_static(ctypes.byref(shape.c()), _ptr(X, dt, "X"),
+                                            _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(counts, torch.int32, "counts"),
+                                            _ptr(offsets, torch.int32, "offsets"), _ptr(row_of, torch.int32, "row_of"),
+                                            _ptr(src_of, torch.int32, "src_of"), _ptr(Xp, dt, "Xp"), _stream(stream))
+    _check(rc, "moe_dispatch_static")
 
 
 def moe_expert_fwd(shape: MoEShape, n_groups, offsets, n_rows, Xin, Wg, Wu, Wd, G, U, H, Yout, ws, stream=None):

@@ -9,6 +9,8 @@
 //                      an assignment among equal experts inside a 64-wide step comes from
 //                      ballots in lane order, so row_of is the same on every run (stable sort).
 //   4. dispatch_rows   one block per token: reads the token row once, writes it to its k rows.
+#include <mutex>
+
 #include "moe_common.h"
 
 namespace moe {
@@ -181,37 +183,14 @@ __global__ __launch_bounds__(256) void dispatch_rows(const uint4* __restrict__ X
 
 }  // namespace moe
 
-extern "C" size_t moe_dispatch_workspace_bytes(const moe_shape_t* shape) {
-  using namespace moe;
-  if (!shape || shape->E < 1 || shape->T < 0 || shape->k < 1) return 0;
-  size_t A = (size_t)shape->T * shape->k;
-  size_t n_chunks = (A + kChunk - 1) / kChunk;
-  return align_up((n_chunks > 0 ? n_chunks : 1) * (size_t)shape->E * sizeof(int32_t), 256);
-}
-
-extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
-                            int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* ws,
-                            size_t ws_bytes, void* stream) {
-  using namespace moe;
-  int rc = check_shape(shape, "moe_dispatch");
-  if (rc) return rc;
-  // with T == 0 only counts and offsets are written (zeros); the per-assignment arrays may be null
-  if (!counts || !offsets || !ws || (shape->T > 0 && (!topk_idx || !row_of || !src_of || !X || !Xp))) {
-    set_error("moe_dispatch: null pointer");
-    return MOE_EINVAL;
-  }
-  if (!aligned16(X) || !aligned16(Xp) || !aligned16(ws)) {
-    set_error("moe_dispatch: X, Xp and ws must be 16-byte aligned");
-    return MOE_EINVAL;
-  }
-  if (ws_bytes < moe_dispatch_workspace_bytes(shape)) {
-    set_error("moe_dispatch: workspace of %zu bytes, need %zu", ws_bytes, moe_dispatch_workspace_bytes(shape));
-    return MOE_EWS;
-  }
-  hipStream_t st = (hipStream_t)stream;
+namespace moe {
+// the four launches of a dispatch; `hist` is scratch of n_chunks * E counters (every one is written
+// by dispatch_count before anything reads it)
+static void dispatch_launch(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                            int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, int32_t* hist,
+                            hipStream_t st) {
   const int A = shape->T * shape->k;
   const int n_chunks = (A + kChunk - 1) / kChunk;
-  int32_t* hist = (int32_t*)ws;
   if (n_chunks > 0) {
     ProfScope prof("dispatch_count", st);
     hipLaunchKernelGGL(dispatch_count, dim3(n_chunks), dim3(64), 0, st, topk_idx, A, shape->E, hist);
@@ -240,5 +219,90 @@ extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32
     }
 #undef MOE_ROWS
   }
+}
+
+// Scratch of moe_dispatch_static: one array per GPU, part of the loaded code object, so that no call
+// allocates.  Host code must not use the symbol's name as an address: the per-device address comes
+// from hipGetSymbolAddress, once per device, and is what the kernels receive.
+constexpr size_t kStaticHistInts = (size_t)MOE_DISPATCH_STATIC_MAX_COUNTERS;
+static __device__ __align__(256) int32_t scratch[kStaticHistInts];
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static int32_t* g_scratch_ptr[kMaxDevices];  // per device, set on the first call with that device current
+
+// address of the current device's scratch array, or NULL with the error text set
+static int32_t* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    set_error("moe_dispatch_static: no current device (or a device index above %d)", kMaxDevices - 1);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      set_error("moe_dispatch_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = (int32_t*)p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace moe
+
+extern "C" size_t moe_dispatch_workspace_bytes(const moe_shape_t* shape) {
+  using namespace moe;
+  if (!shape || shape->E < 1 || shape->T < 0 || shape->k < 1) return 0;
+  size_t A = (size_t)shape->T * shape->k;
+  size_t n_chunks = (A + kChunk - 1) / kChunk;
+  return align_up((n_chunks > 0 ? n_chunks : 1) * (size_t)shape->E * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                            int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* ws,
+                            size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_dispatch");
+  if (rc) return rc;
+  // with T == 0 only counts and offsets are written (zeros); the per-assignment arrays may be null
+  if (!counts || !offsets || !ws || (shape->T > 0 && (!topk_idx || !row_of || !src_of || !X || !Xp))) {
+    set_error("moe_dispatch: null pointer");
+    return MOE_EINVAL;
+  }
+  if (!aligned16(X) || !aligned16(Xp) || !aligned16(ws)) {
+    set_error("moe_dispatch: X, Xp and ws must be 16-byte aligned");
+    return MOE_EINVAL;
+  }
+  if (ws_bytes < moe_dispatch_workspace_bytes(shape)) {
+    set_error("moe_dispatch: workspace of %zu bytes, need %zu", ws_bytes, moe_dispatch_workspace_bytes(shape));
+    return MOE_EWS;
+  }
+  dispatch_launch(shape, X, topk_idx, counts, offsets, row_of, src_of, Xp, (int32_t*)ws, (hipStream_t)stream);
   return launch_status("moe_dispatch");
+}
+
+extern "C" int moe_dispatch_static(const moe_shape_t* shape, const void* X, const int32_t* topk_idx, int32_t* counts,
+                                   int32_t* offsets, int32_t* row_of, int32_t* src_of, void* Xp, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_dispatch_static");
+  if (rc) return rc;
+  if (!counts || !offsets || (shape->T > 0 && (!topk_idx || !row_of || !src_of || !X || !Xp))) {
+    set_error("moe_dispatch_static: null pointer");
+    return MOE_EINVAL;
+  }
+  if (!aligned16(X) || !aligned16(Xp)) {
+    set_error("moe_dispatch_static: X and Xp must be 16-byte aligned");
+    return MOE_EINVAL;
+  }
+  const size_t need = moe_dispatch_workspace_bytes(shape);
+  if (need > kStaticHistInts * sizeof(int32_t)) {
+    set_error("moe_dispatch_static: ceil(T*k / 256) * E = %zu counters exceed the built-in scratch of %zu; use "
+              "moe_dispatch with a workspace", need / sizeof(int32_t), kStaticHistInts);
+    return MOE_EWS;
+  }
+  int32_t* hist = static_scratch();
+  if (!hist) return MOE_ELAUNCH;
+  dispatch_launch(shape, X, topk_idx, counts, offsets, row_of, src_of, Xp, hist, (hipStream_t)stream);
+  return launch_status("moe_dispatch_static");
 }
