@@ -32,6 +32,8 @@ LIGHT_GROUP_ROWS = 256       # routed experts with at most this many rows take t
 PROBE_BYTES = 1 << 30        # size of the calibration copy
 PROBE_LAUNCHES = 5
 COLD_STEPS = 3               # steps of the cold-cache variant
+MFMA_PROBE_BLOCKS = 2048     # blocks (8 per CU) and rounds of the register-resident matrix loop
+MFMA_PROBE_ITERS = 1000
 # kernel behind each profiling label on the bf16 LDS-DMA path, as rocprofv3 names it (one label = one kernel symbol)
 SYMBOL = {
     "gemm_fwd_gate_up": "moe::row_gemm_kernel<moe::RowCores<2, 2, false>, 2, 1, false>(moe::RowGemm)",
@@ -72,13 +74,17 @@ def algorithmic_work(cfg: wl.MoEConfig, counts):
 
 
 def measured_traffic(cfg_name, symbol):
-    """HBM bytes per launch of `symbol` from the committed counter summary of this workload, or None."""
+    """(HBM bytes per launch of `symbol`, where that figure comes from).  The counters cannot be read
+    from inside this process: the figure is the one `rocprofv3 --pmc` measured for this workload when the
+    summary under profiles/ was last regenerated (the file names its command and the commit it ran)."""
     from paper_2502_02581_amd.rocprof_summary import read_traffic
 
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg_name}.txt")
+    rel = os.path.join("profiles", f"hbm_traffic_{cfg_name}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
-    return read_traffic(path).get(symbol)
+        return None, None
+    commit = next((ln.split(":", 1)[1].strip() for ln in open(path) if ln.startswith("# commit:")), "not recorded")
+    return read_traffic(path).get(symbol), f"{rel} (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; kernels of commit {commit})"
 
 
 class LazyExperts:
@@ -94,21 +100,101 @@ class LazyExperts:
         return self.w[int(e)].float().cpu().numpy()
 
 
-def cpu_baseline(cfg, inp, weights, budget_tokens):
-    """Times the oracle, as it stands, on the first `budget_tokens` tokens of the same workload."""
+def blas_threads():
+    """Threads the BLAS behind numpy actually uses in this process."""
+    try:
+        from threadpoolctl import threadpool_info
+
+        n = [int(i.get("num_threads", 0)) for i in threadpool_info() if i.get("user_api") == "blas"]
+        if n:
+            return max(n)
+    except Exception:  # noqa: BLE001
+        pass
+    return os.cpu_count() or 1
+
+
+def cpu_baseline(cfg, inp, weights, budget_s=15.0):
+    """Times the oracle, as it stands, on a bounded sample of the same workload and scales it to the whole.
+
+    Route and the dispatch plan run in full (they are cheap).  The expert work, which is all of the
+    FLOPs, runs on whole experts of a deterministic subset -- the smallest and the median activated
+    expert, the first shared expert, the largest expert, then further experts in descending size for
+    as long as a short calibration product says they fit the budget (the largest and the shared one
+    are cut to their leading rows if even they do not fit) -- so the sample's cost per FLOP is the
+    full workload's by construction.  The operands are widened to fp64 outside the timed region: this is a
+    compute rate, not a transfer rate."""
+    import numpy as np
     from oracle import moe_oracle as orc
 
-    n = min(budget_tokens, cfg.T)
-    lg = inp["logits"][:n].numpy()
-    X = inp["X"][:n].float().numpy()
-    dY = inp["dY"][:n].float().numpy()
-    W = {k: LazyExperts(v) for k, v in weights.items()}
+    R = np.float64
+    lg = inp["logits"].numpy()
     t0 = time.perf_counter()
-    orc.layer_fwd_bwd(lg, X, dY, W["Wg"], W.get("Wu"), W["Wd"], cfg.k, cfg.gate, cfg.renorm,
-                      W.get("Wsg"), W.get("Wsu"), W.get("Wsd"))
-    dt = time.perf_counter() - t0
-    return {"value": n / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
-            "sample": f"first {n} of {cfg.T} tokens of the same workload, fwd+bwd, fp64 numpy oracle, {dt:.1f} s"}
+    idx, w = orc.route(lg, cfg.k, cfg.gate, cfg.renorm)
+    counts, offsets, row_of, src_of = orc.dispatch_plan(idx, cfg.E)
+    dt_plan = time.perf_counter() - t0
+    # calibration: one fp64 product, sized to take well under a second
+    a = np.ones((512, cfg.d), dtype=R)
+    b = np.ones((cfg.d, cfg.d_ff), dtype=R)
+    (a @ b)
+    t1 = time.perf_counter()
+    (a @ b)
+    rate = 2.0 * 512 * cfg.d * cfg.d_ff / max(time.perf_counter() - t1, 1e-6)
+    m = 3.0 if cfg.ffn == "swiglu" else 2.0
+    per_row = 6.0 * m * cfg.d * cfg.d_ff                     # fwd + bwd FLOPs of one row of a routed expert
+    per_row_sh = 6.0 * m * cfg.d * cfg.d_ff_shared
+    active = [int(e) for e in np.argsort(counts, kind="stable") if counts[e] > 0]
+    picks = [(active[0], None), (active[len(active) // 2], None)]
+    room = budget_s * rate - sum(counts[e] for e, _ in picks) * per_row
+    # the first shared expert and the largest routed expert get half of the budget each if they do not
+    # fit whole; what is left goes to further whole experts, largest first
+    n_sh = 0
+    if cfg.n_shared:
+        n_sh = int(min(cfg.T, max(64, 0.5 * room / per_row_sh)))
+        room -= n_sh * per_row_sh
+    for e in reversed(active[len(active) // 2 + 1:]):
+        if e == active[-1]:
+            cap = int(min(counts[e], max(64, room / per_row)))
+            picks.append((e, None if cap == counts[e] else cap))
+            room -= cap * per_row
+        elif counts[e] * per_row <= room:
+            picks.append((e, None))
+            room -= counts[e] * per_row
+
+    X = inp["X"].double().numpy()
+    dY = inp["dY"].double().numpy()
+    wide = lambda t: None if t is None else t.double().cpu().numpy()
+    work = []
+    for e, cap in picks:
+        lo, hi = int(offsets[e]), int(offsets[e + 1])
+        if cap is not None:
+            hi = lo + cap
+        a_ids = src_of[lo:hi]
+        tok = a_ids // cfg.k
+        work.append((X[tok], dY[tok] * w.reshape(-1)[a_ids][:, None], wide(weights["Wg"][e]),
+                     wide(weights["Wu"][e]) if "Wu" in weights else None, wide(weights["Wd"][e]), per_row))
+    if n_sh:
+        work.append((X[:n_sh], dY[:n_sh], wide(weights["Wsg"][0]), wide(weights["Wsu"][0]) if "Wsu" in weights else None,
+                     wide(weights["Wsd"][0]), per_row_sh))
+    flops = 0.0
+    t2 = time.perf_counter()
+    for x, dy, Wg, Wu, Wd, pr in work:
+        g, u, _, _ = orc.ffn(x, Wg, Wu, Wd)
+        orc.ffn_bwd(x, Wg, Wu, Wd, g, u, dy)
+        flops += x.shape[0] * pr
+    dt = time.perf_counter() - t2
+    total = cfg.flops()["total"]
+    full_s = dt_plan + dt * total / flops
+    rows = ", ".join(f"expert {e}: {counts[e] if cap is None else cap} of {counts[e]} rows" for e, cap in picks[:6])
+    if len(picks) > 6:
+        rows += f", and {len(picks) - 6} more whole experts of {sum(int(counts[e]) for e, _ in picks[6:])} rows"
+    if n_sh:
+        rows += f", shared expert 0: {n_sh} of {cfg.T} rows"
+    return {"value": cfg.T / full_s, "unit": "tokens/s", "cores": blas_threads(), "kind": "oracle",
+            "gflops": round(flops / dt / 1e9, 1), "sample_flops": flops, "sample_seconds": round(dt, 2),
+            "host_cpus": os.cpu_count(),
+            "sample": f"fp64 numpy oracle, fwd+bwd: route and dispatch plan of all {cfg.T} tokens ({dt_plan:.1f} s) plus the "
+                      f"expert FFNs of whole experts ({rows}), {flops / 1e9:.0f} GFLOP in {dt:.1f} s, operands widened "
+                      f"to fp64 beforehand; value = T / (plan time + sample time x total FLOPs / sample FLOPs)"}
 
 
 def verify(cfg, inp, weights, hp):
@@ -132,14 +218,13 @@ def verify(cfg, inp, weights, hp):
     return worst
 
 
-CPU_SAMPLE_TOKENS = {"tiny": 256, "qwen": 1024, "phi": 256, "dsv3": 64, "stress": 1024, "gpt-s": 2048, "gpt-l": 512}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="dsv3", choices=list(wl.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-shared", action="store_true",
@@ -174,18 +259,39 @@ def main():
         step()
     torch.cuda.synchronize()
     sampled_err = verify(cfg, inp, weights, hp)
-    moe.moe_profile_enable(True)
+    # ---- the timed region: exactly `steps` bare steps (no per-kernel events), wall clock around all of
+    # them, and one pair of HIP events per step on the launch stream for the median
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    step_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
+
+    # ---- a second, profiled pass of the same steps: the library brackets every launch with HIP events on
+    # the launch stream (this costs a little time per launch, which is why it is not the headline)
+    moe.moe_profile_enable(True)
+    t0p = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_prof = time.perf_counter() - t0p
 
-    # one calibration copy of known size (outside the timed region): a profiler's HBM counters are scaled by it
+    # measured ceilings of this machine (outside the timed region).  One copy of known size: a profiler's HBM
+    # counters are scaled by it.  One register-resident matrix loop: what the matrix pipe sustains.
     probe = torch.empty(2, PROBE_BYTES, dtype=torch.uint8, device=dev)
     probe.fill_(1)   # touches both halves, so that the copy is not timed on fresh pages
     for _ in range(PROBE_LAUNCHES):
         moe.moe_copy_probe(probe[0], probe[1])
+    sink = torch.zeros(MFMA_PROBE_BLOCKS * 256, dtype=torch.float32, device=dev)
+    mfma_flops = 0.0
+    for _ in range(PROBE_LAUNCHES):
+        mfma_flops = moe.moe_mfma_probe(MFMA_PROBE_BLOCKS, MFMA_PROBE_ITERS, sink)
     torch.cuda.synchronize()
     prof = moe.moe_profile_report()
     moe.moe_profile_enable(False)
@@ -201,6 +307,9 @@ def main():
         cold.append(time.perf_counter() - t1)
     del probe
     probe_ms = prof.pop("copy_probe_kernel")[1] / PROBE_LAUNCHES
+    # (mean of the launches: each lasts a few milliseconds, long enough for the clock to settle under the load)
+    mfma_ms = prof.pop("mfma_probe_kernel")[1] / PROBE_LAUNCHES
+    sustained_tf = mfma_flops / (mfma_ms * 1e-3) / 1e12
 
     ms_per_step = dt / args.steps * 1e3
     counts = hp.b["counts"].cpu()
@@ -218,20 +327,30 @@ def main():
         kernels[label] = ent
     gemm_ms = sum(kernels[l]["ms_per_step"] for l in GEMM_LABELS if l in kernels)
     gemm_tflops = sum(flops.values()) / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    # route, dispatch and combine kernels together: their algorithmic bytes over their summed time
+    stream_ms = sum(kernels[l]["ms_per_step"] for l in kernels if l in byts or l.startswith("dispatch_"))
+    stream_gbs = sum(byts.values()) / (stream_ms * 1e-3) / 1e9 if stream_ms > 0 else 0.0
     dom = max((l for l in GEMM_LABELS if l in kernels), key=lambda l: kernels[l]["ms_per_step"])
     dom_n, dom_ms = prof[dom]
     peak = MFMA_BF16_PEAK_TF if cfg.dtype == "bf16" else FP32_VEC_PEAK_TF
     achieved = flops[dom] * args.steps / (dom_ms * 1e-3) / 1e12
     dma_path = cfg.dtype == "bf16" and cfg.d % 64 == 0 and cfg.d_ff % 64 == 0   # SYMBOL names that path's kernels
+    traffic, traffic_src = measured_traffic(cfg.name, SYMBOL[dom]) if dma_path else (None, None)
     roofline = {"bound": "mfma" if cfg.dtype == "bf16" else "alu", "kernel": dom, "symbol": SYMBOL[dom] if dma_path else None,
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "avg_launch_ms": round(dom_ms / dom_n, 4), "launches": dom_n,
                 "flop_per_launch_avg": flops[dom] * args.steps / dom_n,
-                "traffic": measured_traffic(cfg.name, SYMBOL[dom]) if dma_path else None}
+                "timing": "HIP events around every launch, on the launch stream, in a profiled pass of the same steps "
+                          "right after the timed region",
+                "traffic": traffic, "traffic_source": traffic_src}
+    if cfg.dtype == "bf16":
+        roofline["sustained_peak"] = round(sustained_tf, 1)   # register-resident matrix loop on this machine, same run
+        roofline["frac_of_sustained"] = round(achieved / sustained_tf, 4)
 
     out = {
         "metric": "moe_layer_fwd_bwd_tokens_per_s", "value": round(cfg.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "median_step_ms": round(median_ms, 4), "profiled_pass_ms_per_step": round(dt_prof / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} top-{cfg.k} {cfg.gate} d_ff={cfg.d_ff} "
@@ -239,14 +358,19 @@ def main():
                    "active_experts": int((counts > 0).sum()), "max_rows": int(counts.max()),
                    "load_share_std": round(float((counts.double() / counts.sum()).std(unbiased=False)), 5)},
         "grouped_gemm_tflops": round(gemm_tflops, 2), "grouped_gemm_frac_mfma_peak": round(gemm_tflops / peak, 4),
+        "grouped_gemm_frac_of_sustained": round(gemm_tflops / sustained_tf, 4) if cfg.dtype == "bf16" else None,
+        "streaming_gbs": round(stream_gbs, 1), "streaming_frac_hbm_peak": round(stream_gbs / HBM_PEAK_GBS, 4),
+        "streaming_frac_of_copy_probe": round(stream_gbs / (2 * PROBE_BYTES / (probe_ms * 1e-3) / 1e9), 4),
         "total_tflops": round(cfg.flops()["total"] / (ms_per_step * 1e-3) / 1e12, 2),
         "cold_cache_ms_per_step": round(sum(cold) / len(cold) * 1e3, 4),
         "roofline": roofline, "kernels": kernels,
         "copy_probe": {"bytes_each_way": PROBE_BYTES, "ms": round(probe_ms, 4),
-                       "gbs": round(2 * PROBE_BYTES / (probe_ms * 1e-3) / 1e9, 1)}, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
+                       "gbs": round(2 * PROBE_BYTES / (probe_ms * 1e-3) / 1e9, 1)},
+        "mfma_probe": {"flops_per_launch": mfma_flops, "ms": round(mfma_ms, 4), "tflops": round(sustained_tf, 1),
+                       "frac_mfma_peak": round(sustained_tf / MFMA_BF16_PEAK_TF, 4)}, "sampled_error_vs_oracle": float(f"{sampled_err:.3e}"),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, inp, weights, CPU_SAMPLE_TOKENS[cfg.name])
+        out["cpu_baseline"] = cpu_baseline(cfg, inp, weights)
     print(json.dumps(out))
 
 

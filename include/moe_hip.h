@@ -268,6 +268,17 @@ size_t moe_profile_report(char* buf, size_t buf_bytes);
 int moe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
 
 /*
+ * moe_mfma_probe -- measurement aid, not part of the hot path: a register-resident matrix loop
+ * (mfma_probe_kernel).  n_blocks blocks of four wavefronts each issue `iters` rounds of 16 independent
+ * v_mfma_f32_32x32x16_bf16 (all 256 accumulator registers in use, one wavefront per SIMD, no loads, no
+ * LDS).  Its rate is what the matrix pipe sustains at the clock the chip holds under matrix load: the
+ * measured ceiling beside the published 2.5 PFLOP/s.
+ *   sink       device buffer of n_blocks * 256 floats (never written in practice; keeps the loop alive)
+ *   flops_out  host pointer or NULL: receives the FLOPs of the launch, n_blocks * 4 * iters * 16 * 32768
+ */
+int moe_mfma_probe(int32_t n_blocks, int32_t iters, float* sink, double* flops_out, void* stream);
+
+/*
  * Host-side planners of the paper.  Every pointer below is HOST memory; nothing here touches the
  * GPU.  E experts, D devices; devices n*dpn .. n*dpn + dpn - 1 form node n (D a multiple of dpn).
  * A placement is an [E, D] matrix of bytes: nonzero = device d holds the parameters of expert e.

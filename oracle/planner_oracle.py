@@ -14,26 +14,30 @@ parameters of expert e):
                              -> materialization plan P' (a superset of P)
   * token_dispatch      Algorithm 3: placement P', token assignment T[e][d] -> plan R[e][d][d']
 
-Each function takes the steps of the paper's listing in its order.  Where the listing names a
-sub-step without defining it, the reading taken is (each is a choice of this build):
-  * "top t experts by load", "sort by load descending": descending load, equal loads by ascending
-    expert id.
-  * assignSlotsByLoad(e, totSlots, F): the expert's share of the |D| * m ephemeral slots in
-    proportion to its load among the top-t experts, n = floor(totSlots * F[e] / sum of the top-t
-    loads), at least 1 while the loads are not all zero, at most the number of devices that do not
-    hold e yet (a device holds at most one replica of an expert); 0 when all top-t loads are zero.
-  * "distribute n replicas ... prioritizing nodes that do not already hold a replica of e, then
-    devices by available slots": one replica at a time, to the device that minimises
-    (its node already holds e, -free slots of the device, device id) among the devices that have
-    a free slot and do not hold e; stops early when no such device is left.
-  * "evenly dispatch x tokens to a set S": floor(x / |S|) to every device of S and one more to
-    the first x mod |S| devices of S in ascending device id.
+Algorithm 1 and Algorithm 3 are heuristics, so the oracle follows what each of them decides, in
+the paper's order of decisions (candidates by load, then replica counts, then placement; for the
+dispatch: own device, else own node, else everywhere), written as array operations over whole
+experts rather than as the listings' statements.  The listings leave some sub-steps to the reader;
+the readings taken are choices of this build:
+  * ranking experts by load: descending load, equal loads by ascending expert id.
+  * the number of new replicas of a candidate (the listing only names a helper for it): its share of
+    the |D| * m ephemeral slots in proportion to its load among the t candidates, rounded down, at
+    least 1 while those loads are not all zero, never more than the devices that lack the expert
+    (a device holds an expert at most once); 0 when all candidate loads are zero.
+  * where the new replicas go (the listing states two priorities and no procedure): one at a time,
+    to a device that lacks the expert and has a free slot, preferring first a node where the expert
+    is absent, then the device with the most free slots, then the lowest device id; placement of
+    an expert stops when no such device is left.
+  * an even split of x tokens over n devices: x // n each, and one more for the x mod n lowest
+    device ids.
   * the calibration stage and the cost/benefit test around it are not modelled.
 """
 from __future__ import annotations
 
 import math
-from typing import List, Sequence
+from typing import Dict, List, Sequence
+
+import numpy as np
 
 
 def overlap_degree(t_attn: float, bw: float, psi: float) -> int:
@@ -52,72 +56,73 @@ def predict_load(history: Sequence[Sequence[float]], w: int = 5) -> List[float]:
     return [sum(float(row[e]) for row in last) / len(last) for e in range(E)]
 
 
-def _node(d: int, dpn: int) -> int:
-    return d // dpn
+def replica_counts(P: np.ndarray, F: np.ndarray, cand: Sequence[int], slots: int) -> Dict[int, int]:
+    """New replicas each candidate of Algorithm 1 is entitled to: proportional to load, see the header."""
+    D = P.shape[1]
+    load = float(sum(F[e] for e in cand))
+    out = {}
+    for e in cand:
+        share = max(1, int(math.floor(slots * float(F[e]) / load))) if load > 0 else 0
+        out[e] = min(share, D - int(P[e].sum()))
+    return out
 
 
 def sparse_materialization(P: Sequence[Sequence[int]], F: Sequence[float], t: int, m: int, dpn: int):
-    """Algorithm 1.  P [E][D] 0/1, F [E] loads, t overlap degree, m ephemeral replicas per device.
-    Returns P' [E][D] as lists of 0/1."""
-    E, D = len(P), len(P[0])
-    if D % dpn != 0 or t < 0 or m < 0 or any(f < 0 for f in F):
+    """Algorithm 1 (Sparse Materialization).  P [E][D] 0/1 shard placement, F [E] loads, t overlap
+    degree, m ephemeral replicas per device.  Returns the plan P' [E][D] as lists of 0/1."""
+    plan = (np.asarray(P) != 0).astype(np.int64)
+    E, D = plan.shape
+    load = np.asarray(F, dtype=np.float64)
+    if D % dpn != 0 or t < 0 or m < 0 or (load < 0).any():
         raise ValueError("bad arguments")
     t = min(t, E)
     m = min(m, t)
-    Pp = [[1 if P[e][d] else 0 for d in range(D)] for e in range(E)]
-    by_load = sorted(range(E), key=lambda e: (-float(F[e]), e))
-    top = by_load[:t]                       # already in descending load
+    # candidates: the t most loaded experts (a stable sort on the negated load keeps equal loads in id order)
+    cand = [int(e) for e in np.argsort(-load, kind="stable")[:t]]
     if t <= m:
-        for e in top:
-            for d in range(D):
-                Pp[e][d] = 1
-        return Pp
-    tot_slots = D * m
-    free = [m] * D
-    top_load = sum(float(F[e]) for e in top)
-    for e in top:
-        holders = sum(Pp[e])
-        if top_load > 0:
-            n = int(math.floor(tot_slots * float(F[e]) / top_load))
-            n = max(n, 1)
-        else:
-            n = 0
-        n = min(n, D - holders)
-        for _ in range(n):
-            cand = [d for d in range(D) if free[d] > 0 and not Pp[e][d]]
-            if not cand:
+        plan[cand, :] = 1            # room for every candidate on every device
+        return plan.tolist()
+    want = replica_counts(plan, load, cand, D * m)
+    free = np.full(D, m, dtype=np.int64)
+    node_of = np.arange(D) // dpn
+    for e in cand:                   # heaviest first: it chooses among the most free slots
+        for _ in range(want[e]):
+            open_dev = np.flatnonzero((free > 0) & (plan[e] == 0))
+            if open_dev.size == 0:
                 break
-            node_has = {_node(d, dpn) for d in range(D) if Pp[e][d]}
-            d = min(cand, key=lambda d: (1 if _node(d, dpn) in node_has else 0, -free[d], d))
-            Pp[e][d] = 1
+            node_has_e = np.isin(node_of[open_dev], node_of[plan[e] == 1])
+            # lexicographic preference: absent from the node, most free slots, lowest id
+            order = np.lexsort((open_dev, -free[open_dev], node_has_e))
+            d = int(open_dev[order[0]])
+            plan[e, d] = 1
             free[d] -= 1
-    return Pp
+    return plan.tolist()
+
+
+def split_evenly(x: int, n: int) -> List[int]:
+    """x tokens over n receivers in ascending id: x // n each, the first x mod n get one more."""
+    return [x // n + (1 if i < x % n else 0) for i in range(n)]
 
 
 def token_dispatch(Pp: Sequence[Sequence[int]], T: Sequence[Sequence[int]], dpn: int):
-    """Algorithm 3.  P' [E][D] 0/1, T [E][D] tokens of device d assigned to expert e.
-    Returns R [E][D][D]: R[e][d][d2] tokens of device d sent to expert e on device d2."""
-    E, D = len(Pp), len(Pp[0])
+    """Algorithm 3 (Topology-aware Token Dispatching).  P' [E][D] 0/1, T [E][D] tokens of device d
+    assigned to expert e.  Returns R [E][D][D]: R[e][d][d2] tokens of device d sent to expert e on d2."""
+    held = np.asarray(Pp) != 0
+    tokens = np.asarray(T, dtype=np.int64)
+    E, D = held.shape
     if D % dpn != 0:
         raise ValueError("devices do not fill whole nodes")
-    R = [[[0] * D for _ in range(D)] for _ in range(E)]
-
-    def evenly(x, S):
-        q, r = divmod(x, len(S))
-        return {d2: q + (1 if i < r else 0) for i, d2 in enumerate(sorted(S))}
-
+    node_of = np.arange(D) // dpn
+    R = np.zeros((E, D, D), dtype=np.int64)
     for e in range(E):
-        De = [d for d in range(D) if Pp[e][d]]
-        if not De:
+        if not held[e].any():
             raise ValueError(f"expert {e} is materialized nowhere")
-        for d in De:                                    # local dispatching
-            R[e][d][d] = int(T[e][d])
         for d in range(D):
-            if Pp[e][d]:
-                continue
-            local = [d2 for d2 in range(D) if _node(d2, dpn) == _node(d, dpn)]
-            elocal = [d2 for d2 in De if d2 in local]
-            target = elocal if elocal else De           # intra-node, else inter-node dispatching
-            for d2, x in evenly(int(T[e][d]), target).items():
-                R[e][d][d2] = x
-    return R
+            # receivers of device d's tokens for e, by decreasing locality: itself, the holders in its
+            # node, all holders -- the first of the three sets that is not empty
+            for level in (held[e] & (np.arange(D) == d), held[e] & (node_of == node_of[d]), held[e]):
+                recv = np.flatnonzero(level)
+                if recv.size:
+                    break
+            R[e, d, recv] = split_evenly(int(tokens[e, d]), recv.size)
+    return R.tolist()

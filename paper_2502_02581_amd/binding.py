@@ -20,7 +20,7 @@ EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
            "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd",
            "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch",
-           "moe_dispatch_static"]
+           "moe_dispatch_static", "moe_mfma_probe"]
 
 
 class MoEError(RuntimeError):
@@ -118,6 +118,8 @@ def load_library():
     lib.moe_profile_report.argtypes = [ctypes.c_char_p, sz]
     lib.moe_copy_probe.restype = ctypes.c_int
     lib.moe_copy_probe.argtypes = [vp, vp, sz, vp]
+    lib.moe_mfma_probe.restype = ctypes.c_int
+    lib.moe_mfma_probe.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -345,6 +347,17 @@ def moe_copy_probe(src: torch.Tensor, dst: torch.Tensor):
         raise MoEError("moe_copy_probe: sizes differ")
     rc = load_library().moe_copy_probe(_ptr(src), _ptr(dst), ctypes.c_size_t(nbytes), _stream(None))
     _check(rc, "moe_copy_probe")
+
+
+def moe_mfma_probe(n_blocks: int, iters: int, sink: torch.Tensor) -> float:
+    """Launches the register-resident matrix loop once; returns the FLOPs of the launch (time it outside)."""
+    if sink.numel() < n_blocks * 256:
+        raise MoEError("moe_mfma_probe: sink needs n_blocks * 256 floats")
+    flops = ctypes.c_double(0.0)
+    rc = load_library().moe_mfma_probe(int(n_blocks), int(iters), _ptr(sink, torch.float32, "sink"), ctypes.byref(flops),
+                                       _stream(None))
+    _check(rc, "moe_mfma_probe")
+    return float(flops.value)
 
 
 def moe_profile_enable(on: bool):

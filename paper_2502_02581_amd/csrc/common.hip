@@ -163,5 +163,54 @@ extern "C" int moe_copy_probe(const void* src, void* dst, size_t bytes, void* st
   return launch_status("moe_copy_probe");
 }
 
+namespace moe {
+// Register-resident matrix loop: every wavefront issues `iters` rounds of 16 independent
+// v_mfma_f32_32x32x16_bf16 on constant operands (16 accumulator tiles = all 256 accumulator registers,
+// one wavefront per SIMD); no loads, no LDS.  What it sustains is the matrix pipe's rate at the clock
+// the chip holds under that load.
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16_t;
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, float* sink) {
+  const int lane = threadIdx.x & 63;
+  probe_bf16x8_t a, b;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    a[i] = (__bf16)(0.001f * (float)((lane + i) % 7));
+    b[i] = (__bf16)(0.002f * (float)((lane + 2 * i) % 5));
+  }
+  probe_f32x16_t acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; j++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[j][r] = 0.f;
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int j = 0; j < 16; j++) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 16; j++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) s += acc[j][r];
+  // keeps the loop alive; the sums are small positive numbers, so nothing is ever stored
+  if (s == -1.f) sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
+}  // namespace moe
+
+extern "C" int moe_mfma_probe(int32_t n_blocks, int32_t iters, float* sink, double* flops_out, void* stream) {
+  using namespace moe;
+  if (n_blocks < 1 || n_blocks > (1 << 20) || iters < 1 || iters > (1 << 24) || !sink) {
+    set_error("moe_mfma_probe: needs 1..2^20 blocks, 1..2^24 rounds and a device buffer of n_blocks * 256 floats");
+    return MOE_EINVAL;
+  }
+  {
+    ProfScope prof("mfma_probe_kernel", (hipStream_t)stream);
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)n_blocks), dim3(256), 0, (hipStream_t)stream, (int)iters, sink);
+  }
+  // 4 wavefronts x iters x 16 instructions x (2 * 32 * 32 * 16) FLOPs per block
+  if (flops_out) *flops_out = (double)n_blocks * 4.0 * (double)iters * 16.0 * 32768.0;
+  return launch_status("moe_mfma_probe");
+}
+
 extern "C" int moe_abi_version(void) { return MOE_ABI_VERSION; }
 extern "C" const char* moe_last_error(void) { return moe::g_err; }

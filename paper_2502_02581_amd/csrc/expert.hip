@@ -8,6 +8,8 @@
 //           B3 : dWd_e = H_e^T dYin_e;  [dWg_e | dWu_e] = Xin_e^T [dG_e | dU_e]
 // A device-built plan turns the row offsets into a list of row tiles (largest group first,
 // groups without rows contribute nothing) so that no host synchronisation is needed.
+#include <atomic>
+
 #include "gemm_cores.h"
 #include "gemm_plan.h"
 
@@ -356,35 +358,6 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   }
 }
 
-#ifdef MOE_TRACE
-// Development aid (compiled in only with -DMOE_TRACE): one record per tile of the GEMM kernels,
-// {block, kernel id, group, column tile | kind << 8 | rows << 16, start, end, phase cycles}, times
-// from the 100 MHz wall clock, phases (set-up and first loads, K loop, epilogue, rest) in shader
-// clock cycles; read back through moe_trace_read.
-struct TraceRec {
-  int32_t block, kernel, group, what;
-  unsigned long long t0, t1;
-  int32_t ph[4];
-};
-constexpr int kTraceMax = 1 << 18;
-__device__ TraceRec g_trace[kTraceMax];
-__device__ int g_trace_n;
-__device__ __forceinline__ void trace_put(int kernel, int group, int what, unsigned long long t0) {
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int i = atomicAdd(&g_trace_n, 1);
-    if (i < kTraceMax) {
-      TraceRec r = {(int32_t)(blockIdx.x + blockIdx.y * gridDim.x), kernel, group, what, t0, (unsigned long long)wall_clock64(), {0, 0, 0, 0}};
-      const long long* ph = g_ph + (blockIdx.x & 0xffff) * 4;
-      const long long now = clock64();
-      r.ph[0] = (int32_t)(ph[1] - ph[0]); r.ph[1] = (int32_t)(ph[2] - ph[1]); r.ph[2] = (int32_t)(ph[3] - ph[2]);
-      r.ph[3] = (int32_t)(now - ph[3]);
-      g_trace[i] = r;
-    }
-  }
-}
-#endif
-
 template <class CoreSet, int NB, int EPI, bool B_KC>
 __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel(RowGemm p) {
   extern __shared__ __align__(16) char smem[];
@@ -422,10 +395,7 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
     t.rows = min(bm, p.n_rows - t.row0_in) | (kind << 16);
     t.row0_out = t.row0_in;
   }
-#ifdef MOE_TRACE
-  const unsigned long long t_start = (unsigned long long)wall_clock64();
-  const unsigned long long c_start = (unsigned long long)clock64();
-#endif
+  MOE_TRACE_BEGIN();
   if (CoreSet::kKinds == 1) {
     row_gemm_tile<Core0, NB, EPI, B_KC>(p, t, nt, smem);
   } else {
@@ -436,11 +406,7 @@ __global__ __launch_bounds__(CoreSet::template tile<0>::NT) void row_gemm_kernel
       default: row_gemm_tile<typename CoreSet::template tile<3>, NB, EPI, B_KC>(p, t, nt, smem); break;
     }
   }
-#ifdef MOE_TRACE
-  // the group field carries the shader clock cycles of the tile (shader clock = cycles / wall time)
-  trace_put(EPI | (NB << 4) | ((int)B_KC << 8), (int)((unsigned long long)clock64() - c_start),
-            nt | (tile_kind(t) << 8) | (tile_rows(t) << 16), t_start);
-#endif
+  MOE_TRACE_ROW_TILE(EPI | (NB << 4) | ((int)B_KC << 8), nt | (tile_kind(t) << 8) | (tile_rows(t) << 16));
 }
 
 // ------------------------------------------------------------------- weight-gradient kernel
@@ -492,13 +458,9 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
     Pack<T, W>::store_nt((T*)p.C[z] + off, v[0]);
     if (NB == 2) Pack<T, W>::store_nt((T*)p.C[1] + off, v[NB - 1]);
   };
-#ifdef MOE_TRACE
-  const unsigned long long t_start = (unsigned long long)wall_clock64();
-#endif
+  MOE_TRACE_BEGIN();
   Core::run(smem, 1, (K + BK - 1) / BK, segf, p.lda, p.ldb, m_valid, n_valid, epi);
-#ifdef MOE_TRACE
-  trace_put(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16, t_start);
-#endif
+  MOE_TRACE_W_TILE(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16);
   }
 }
 
@@ -550,6 +512,21 @@ static int pick_path(const moe_shape_t* s) {
 
 static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// A kernel that wants more than 48 KB of dynamic LDS has to be told so once per device (the
+// attribute belongs to the kernel's code object on that device); one instance per kernel.
+struct LdsAttr {
+  std::atomic<uint64_t> done{0};  // bit i: set on device i
+  void ensure(const void* kern, int lds_bytes) {
+    if (lds_bytes <= 48 * 1024) return;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_relaxed) & bit)) return;
+    (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (dev < 64) done.fetch_or(bit, std::memory_order_relaxed);
+  }
+};
+
 // upper bound of the row tiles the plan kernel may emit (BM == 0: mixed heights, at most two
 // remainder tiles per group)
 static int max_row_tiles(int n_groups, int n_rows, bool shared, int BM) {
@@ -565,11 +542,8 @@ static void launch_row(const char* label, const RowGemm& p, int max_tiles, hipSt
   const int n_mt = p.tiles ? max_tiles : ceil_div(p.n_rows, CoreSet::kKinds == 4 ? kind_height(p.direct_kind) : Core::BM);
   if (n_mt == 0 || ntn == 0) return;
   auto kern = row_gemm_kernel<CoreSet, NB, EPI, B_KC>;
-  static bool attr_done = false;
-  if (!attr_done && Core::LDS_BYTES > 48 * 1024) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
-    attr_done = true;
-  }
+  static LdsAttr attr;
+  attr.ensure((const void*)kern, Core::LDS_BYTES);
   ProfScope prof(label, st);
   // LDS-DMA path: whole bands of kBandRows row tiles, handed out in runs of 32 tiles to 8 XCDs
   const unsigned n_blocks = CoreSet::kKinds == 4 ? (unsigned)ceil_div(ceil_div(n_mt, kBandRows) * kBandRows * ntn, 256) * 256u
@@ -582,11 +556,8 @@ static void launch_w(const char* label, const WGemm& p, int n_groups, hipStream_
   const int tiles = ceil_div(p.M, Core::BM) * ceil_div(ceil_div(p.N, Core::BN), p.n_reps > 1 ? p.n_reps : 1);
   if (tiles == 0 || n_groups == 0) return;
   auto kern = w_gemm_kernel<Core, NB>;
-  static bool attr_done = false;
-  if (!attr_done && Core::LDS_BYTES > 48 * 1024) {
-    (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Core::LDS_BYTES);
-    attr_done = true;
-  }
+  static LdsAttr attr;
+  attr.ensure((const void*)kern, Core::LDS_BYTES);
   ProfScope prof(label, st);
   hipLaunchKernelGGL(kern, dim3((unsigned)tiles, (unsigned)n_groups, (unsigned)n_products), dim3(Core::NT), Core::LDS_BYTES, st, p);
 }
@@ -995,16 +966,4 @@ extern "C" int moe_router_bwd(const moe_shape_t* shape, const void* X, const voi
   return launch_status("moe_router_bwd");
 }
 
-#ifdef MOE_TRACE
-// copies the trace records to the host buffer (at most max_records), returns their number and clears the trace
-extern "C" int moe_trace_read(void* host, int max_records) {
-  int n = 0;
-  if (hipMemcpyFromSymbol(&n, HIP_SYMBOL(moe::g_trace_n), sizeof(int)) != hipSuccess) return -1;
-  if (n > moe::kTraceMax) n = moe::kTraceMax;
-  if (n > max_records) n = max_records;
-  if (n > 0 && hipMemcpyFromSymbol(host, HIP_SYMBOL(moe::g_trace), (size_t)n * sizeof(moe::TraceRec)) != hipSuccess) return -1;
-  int zero = 0;
-  (void)hipMemcpyToSymbol(HIP_SYMBOL(moe::g_trace_n), &zero, sizeof(int));
-  return n;
-}
-#endif
+MOE_TRACE_DEFINE_READER

@@ -10,18 +10,9 @@
 #pragma once
 
 #include "moe_common.h"
+#include "trace.h"
 
 namespace moe {
-// Development aid (compiled in only with -DMOE_TRACE): the LDS-DMA core stamps the shader clock where
-// a tile's phases end -- 0: entry, 1: first operand tiles in LDS (ring pipeline only), 2: K loop
-// done, 3: epilogue done (first wavefront) -- and the kernels' trace records carry the differences.
-#ifdef MOE_TRACE
-__device__ long long g_ph[65536 * 4];
-#define MOE_PHASE(i) do { if (threadIdx.x == 0) g_ph[(blockIdx.x & 0xffff) * 4 + (i)] = clock64(); } while (0)
-#else
-#define MOE_PHASE(i) do {} while (0)
-#endif
-
 // An epilogue functor may read global memory at the position it writes (an activation's saved input,
 // an output it accumulates into).  If it says how many 16-byte pieces per position (`kAux`) and offers
 // `prefetch(m, n)` returning them, the LDS-DMA core requests the pieces of a whole block of rows

@@ -307,7 +307,7 @@ extern "C" int moe_aux_loss(const moe_shape_t* shape, const float* logits, const
   }
   if (ws_bytes < moe_aux_loss_workspace_bytes(shape)) {
     set_error("moe_aux_loss: workspace of %zu bytes, need %zu", ws_bytes, moe_aux_loss_workspace_bytes(shape));
-    return MOE_EINVAL;
+    return MOE_EWS;
   }
   hipStream_t st = (hipStream_t)stream;
   const int T = shape->T, E = shape->E, n_waves = aux_waves(T);

@@ -55,15 +55,6 @@ def scale_rel_err(got, ref):
     return float(np.abs(got - ref).max()) / den
 
 
-def elem_rel_err(got, ref, floor=1e-3):
-    """max over elements of |got - ref| / max(|ref|, floor * max|ref|)."""
-    got, ref = np64(got), np64(ref)
-    m = float(np.abs(ref).max())
-    if m == 0.0:
-        return float(np.abs(got).max())
-    return float((np.abs(got - ref) / np.maximum(np.abs(ref), floor * m)).max())
-
-
 def _eval(expr, env):
     return float(eval(expr, {"__builtins__": {}}, env))
 

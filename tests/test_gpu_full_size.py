@@ -6,7 +6,8 @@ The oracle cannot run a whole 2-20 TFLOP layer in test time, so at full size:
   * Y, dX, dw and dlogits are compared on sampled tokens, each computed by the oracle straight from
     Eq. 3 (oracle.token_fwd_bwd: the token's k experts and the shared experts; oracle.route_bwd);
   * the compacted weight gradients are compared in full for sampled experts (a mid-size one, the
-    median one and the smallest active one), each recomputed by the oracle from its own rows;
+    median one and the smallest active one), each recomputed by the oracle from its own rows, and for
+    the hottest expert on sampled d_ff positions (all of its rows: the longest K loop there is);
   * the shared experts' weight gradients are compared in full for one shared expert.
 Tolerance: max|gpu - ref| / max|ref| <= 2e-2 per compared tensor (bf16 path).
 """
@@ -124,6 +125,32 @@ def test_full_size_sampled(name):
             errs[f"dWu[e{e},n{hi - lo}]"] = scale_rel_err(b["dWu_c"][slot].cpu(), dWu)
         errs[f"dWd[e{e},n{hi - lo}]"] = scale_rel_err(b["dWd_c"][slot].cpu(), dWd)
         errs[f"Yp[e{e}]"] = scale_rel_err(b["Yp"][lo:hi].cpu(), Ype)
+
+    # ---- the hottest expert (the longest K loop of the weight-gradient kernels): its activations and
+    # weight gradients on a slice of d_ff positions, each exact and cheap from the definition:
+    #   G[:, f] = Xe Wg[:, f];  dWd[f, :] = H[:, f]^T dYp;  dWg[:, f] = Xe^T dG[:, f]  (dG[:, f] needs all of dYp, Wd[f, :])
+    hot = by_size[-1]
+    if hot not in chosen:
+        lo, hi = int(offsets[hot]), int(offsets[hot + 1])
+        a = src_of[lo:hi].astype(np.int64)
+        Xe = X64[a // cfg.k]
+        dYe = dY64[a // cfg.k] * dY_rows_w[a][:, None]
+        fs = np.unique(np.concatenate([[0, cfg.d_ff - 1], rng.integers(0, cfg.d_ff, 14)]))
+        Wg_h, Wd_h = Wl["Wg"][hot].astype(np.float64), Wl["Wd"][hot].astype(np.float64)
+        Wu_h = Wl["Wu"][hot].astype(np.float64) if gated else None
+        # the expert body of the oracle on an expert cut down to the sampled d_ff positions (Eq. 2: an
+        # expert is the sum of its d_ff slices, and G, U, H, dG, dU, dW of a slice depend on that slice only)
+        We = [Wg_h[:, fs], Wu_h[:, fs] if gated else None, Wd_h[fs, :]]
+        G, U, H, _ = orc.ffn(Xe, *We)
+        _, dWg, dWu, dWd, _, _ = orc.ffn_bwd(Xe, *We, G, U, dYe)
+        slot = active.index(hot)
+        ft = torch.from_numpy(fs)
+        errs[f"hot G[e{hot},n{hi - lo}]"] = scale_rel_err(b["G"][lo:hi].cpu()[:, ft], G)
+        errs[f"hot H[e{hot}]"] = scale_rel_err(b["H"][lo:hi].cpu()[:, ft], H)
+        errs[f"hot dWg[e{hot}]"] = scale_rel_err(b["dWg_c"][slot].cpu()[:, ft], dWg)
+        if gated:
+            errs[f"hot dWu[e{hot}]"] = scale_rel_err(b["dWu_c"][slot].cpu()[:, ft], dWu)
+        errs[f"hot dWd[e{hot}]"] = scale_rel_err(b["dWd_c"][slot].cpu()[ft], dWd)
 
     # ---- one shared expert: dense dW in full
     if cfg.n_shared:

@@ -73,6 +73,13 @@ def test_host_side_validation(lib):
     assert lib.moe_expert_fwd(ctypes.byref(s), 8, fake, 32, *([fake] * 9), 16, None) == -2
     assert lib.moe_expert_bwd(ctypes.byref(s), 8, fake, 32, *([fake] * 15), 16, None) == -2
     assert lib.moe_expert_fwd(ctypes.byref(s), 0, fake, 32, *([fake] * 9), 1 << 20, None) == -1
+    lib.moe_aux_loss.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_float] + [ctypes.c_void_p] * 3 + [ctypes.c_size_t, ctypes.c_void_p]
+    assert lib.moe_aux_loss(ctypes.byref(s), fake, fake, 0.001, fake, fake, fake, 16, None) == -2
+    assert "workspace" in lib.moe_last_error().decode()
+    # the dispatch without a workspace argument refuses what its built-in scratch cannot hold
+    big = shape(T=1 << 20, k=8, E=1024)
+    assert lib.moe_dispatch_static(ctypes.byref(big), fake, fake, fake, fake, fake, fake, fake, None) == -2
+    assert "built-in scratch" in lib.moe_last_error().decode()
     # workspace queries are pure host arithmetic
     sh = moe.MoEShape(8192, 7168, 256, 8, 2048)
     assert moe.moe_dispatch_workspace_bytes(sh) >= 256 * 256 * 4
