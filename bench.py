@@ -229,6 +229,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--overlap-shared", action="store_true",
                     help="run the shared experts on a second stream (per-kernel durations then overlap)")
+    ap.add_argument("--gather", action="store_true",
+                    help="routed experts read X and dY in place through src_of (moe_expert_*_gather)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is the one-GPU hot path; it has no multi-GPU mode (run with --gpus 1)",
@@ -248,7 +250,7 @@ def main():
     g = {k: v.to(dev) for k, v in inp.items()}
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
     hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, overlap_shared=args.overlap_shared,
-                        aux_alpha=cfg.aux_alpha)
+                        aux_alpha=cfg.aux_alpha, gather=args.gather)
     sh = [weights.get("Wsg"), weights.get("Wsu"), weights.get("Wsd")]
 
     def step():

@@ -229,6 +229,29 @@ int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const int32_t* of
                    size_t ws_bytes, void* stream);
 
 /*
+ * moe_expert_fwd_gather / moe_expert_bwd_gather -- the two expert calls in grouped mode (routed experts:
+ * n_groups = shape->E, n_rows = shape->T * shape->k) reading token rows in place instead of permuted
+ * copies: tokens whose experts are all local need no exchange (the local branch of Algorithm 3), so the
+ * grouped order can be an index, src_of from moe_dispatch, rather than a second copy of the data.
+ *   forward:  row r of every product reads X[src_of[r] / k, :] (X [T, d]); Xp is not read.
+ *             G, U, H, Yout exactly as moe_expert_fwd would compute them from Xp (same bits).
+ *   backward: dH = (dY[src_of[r] / k, :] Wd^T) * topk_w[src_of[r]] row by row, i.e. the weight of the
+ *             combine is applied after the product, in fp32, instead of to a rounded copy of the rows;
+ *             everything else as moe_expert_bwd.  Xp and dYp = moe_combine_bwd's output are still read,
+ *             by the weight gradients only (there the gathered dimension would be the one summed over).
+ * Byte offsets into X and dY are 32 bits: T * d * element size must stay below 4 GiB (MOE_EINVAL
+ * otherwise).  Workspaces as for moe_expert_fwd / moe_expert_bwd with shared = 0.
+ */
+int moe_expert_fwd_gather(const moe_shape_t* shape, const int32_t* offsets, const int32_t* src_of, const void* X,
+                          const void* Wg, const void* Wu, const void* Wd, void* G, void* U, void* H, void* Yout,
+                          void* ws, size_t ws_bytes, void* stream);
+int moe_expert_bwd_gather(const moe_shape_t* shape, const int32_t* offsets, const int32_t* src_of, const void* Xp,
+                          const void* Wg, const void* Wu, const void* Wd, const void* G, const void* U,
+                          const void* H, const void* dY, const float* topk_w, const void* dYp, void* dXp,
+                          int32_t* active_ids, int32_t* n_active, void* dWg_c, void* dWu_c, void* dWd_c, void* ws,
+                          size_t ws_bytes, void* stream);
+
+/*
  * moe_combine -- the weighted sum of Eq. 3:
  *   Y[t, :] = Yadd[t, :] + sum_j topk_w[t, j] * Yp[row_of[t*k + j], :]
  * accumulated in fp32 and rounded once.  topk_w == NULL means unit weights (this is then the

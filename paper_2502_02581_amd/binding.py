@@ -20,7 +20,7 @@ EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
            "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd",
            "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch",
-           "moe_dispatch_static", "moe_mfma_probe"]
+           "moe_dispatch_static", "moe_mfma_probe", "moe_expert_fwd_gather", "moe_expert_bwd_gather"]
 
 
 class MoEError(RuntimeError):
@@ -108,6 +108,10 @@ def load_library():
     lib.moe_expert_fwd.argtypes = [shp, i32, vp, i32] + [vp] * 9 + [sz, vp]
     lib.moe_expert_bwd.restype = ctypes.c_int
     lib.moe_expert_bwd.argtypes = [shp, i32, vp, i32] + [vp] * 15 + [sz, vp]
+    lib.moe_expert_fwd_gather.restype = ctypes.c_int
+    lib.moe_expert_fwd_gather.argtypes = [shp] + [vp] * 11 + [sz, vp]
+    lib.moe_expert_bwd_gather.restype = ctypes.c_int
+    lib.moe_expert_bwd_gather.argtypes = [shp] + [vp] * 19 + [sz, vp]
     lib.moe_combine.restype = ctypes.c_int
     lib.moe_combine.argtypes = [shp, vp, vp, vp, vp, vp, vp]
     lib.moe_combine_bwd.restype = ctypes.c_int
@@ -324,6 +328,28 @@ def moe_expert_bwd(shape: MoEShape, n_groups, offsets, n_rows, Xin, Wg, Wu, Wd, 
     _check(rc, "moe_expert_bwd")
 
 
+def moe_expert_fwd_gather(shape: MoEShape, offsets, src_of, X, Wg, Wu, Wd, G, U, H, Yout, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_expert_fwd_gather(
+        ctypes.byref(shape.c()), _ptr(offsets, torch.int32, "offsets"), _ptr(src_of, torch.int32, "src_of"),
+        _ptr(X, dt, "X"), _ptr(Wg, dt, "Wg"), _ptr(Wu, dt, "Wu"), _ptr(Wd, dt, "Wd"), _ptr(G, dt, "G"), _ptr(U, dt, "U"),
+        _ptr(H, dt, "H"), _ptr(Yout, dt, "Yout"), _ptr(ws, None, "ws"), ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_expert_fwd_gather")
+
+
+def moe_expert_bwd_gather(shape: MoEShape, offsets, src_of, Xp, Wg, Wu, Wd, G, U, H, dY, topk_w, dYp, dXp, active_ids,
+                          n_active, dWg_c, dWu_c, dWd_c, ws, stream=None):
+    dt = shape.torch_dtype
+    rc = load_library().moe_expert_bwd_gather(
+        ctypes.byref(shape.c()), _ptr(offsets, torch.int32, "offsets"), _ptr(src_of, torch.int32, "src_of"),
+        _ptr(Xp, dt, "Xp"), _ptr(Wg, dt, "Wg"), _ptr(Wu, dt, "Wu"), _ptr(Wd, dt, "Wd"), _ptr(G, dt, "G"), _ptr(U, dt, "U"),
+        _ptr(H, dt, "H"), _ptr(dY, dt, "dY"), _ptr(topk_w, torch.float32, "topk_w"), _ptr(dYp, dt, "dYp"),
+        _ptr(dXp, dt, "dXp"), _ptr(active_ids, torch.int32, "active_ids"), _ptr(n_active, torch.int32, "n_active"),
+        _ptr(dWg_c, dt, "dWg_c"), _ptr(dWu_c, dt, "dWu_c"), _ptr(dWd_c, dt, "dWd_c"), _ptr(ws, None, "ws"),
+        ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_expert_bwd_gather")
+
+
 def moe_combine(shape: MoEShape, Yp, row_of, topk_w, Yadd, Y, stream=None):
     dt = shape.torch_dtype
     rc = load_library().moe_combine(ctypes.byref(shape.c()), _ptr(Yp, dt, "Yp"), _ptr(row_of, torch.int32, "row_of"),
@@ -393,8 +419,9 @@ class MoEHotPath:
     """
 
     def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0",
-                 overlap_shared: bool = False, aux_alpha: float = 0.0):
+                 overlap_shared: bool = False, aux_alpha: float = 0.0, gather: bool = False):
         self.shape, self.S, self.Fs, self.device = shape, n_shared, d_ff_shared, torch.device(device)
+        self.gather = bool(gather)  # routed experts read X and dY through src_of (moe_expert_*_gather)
         self.aux_alpha = float(aux_alpha)
         self.overlap = bool(overlap_shared and n_shared)
         s, dt, dev = shape, shape.torch_dtype, self.device
@@ -464,7 +491,11 @@ class MoEHotPath:
         moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
         if self.aux_alpha > 0:
             moe_aux_loss(s, logits, b["counts"], self.aux_alpha, b["aux_P"], b["aux_loss"], self.ws, stream)
-        moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
+        if self.gather:
+            moe_expert_fwd_gather(s, b["offsets"], b["src_of"], X, Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws,
+                                  stream)
+        else:
+            moe_expert_fwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws, stream)
         if self.overlap:
             self._join(main)
         elif self.S:
@@ -481,8 +512,13 @@ class MoEHotPath:
             moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
                            b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws_shared, self.side)
         moe_combine_bwd(s, dY, b["Yp"], b["row_of"], b["topk_w"], b["dYp"], b["dw"], stream)
-        moe_expert_bwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["dYp"], b["dXp"],
-                       b["active_ids"], b["n_active"], b["dWg_c"], b["dWu_c"], b["dWd_c"], self.ws, stream)
+        if self.gather:
+            moe_expert_bwd_gather(s, b["offsets"], b["src_of"], b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], dY,
+                                  b["topk_w"], b["dYp"], b["dXp"], b["active_ids"], b["n_active"], b["dWg_c"],
+                                  b["dWu_c"], b["dWd_c"], self.ws, stream)
+        else:
+            moe_expert_bwd(s, s.E, b["offsets"], A, b["Xp"], Wg, Wu, Wd, b["G"], b["U"], b["H"], b["dYp"], b["dXp"],
+                           b["active_ids"], b["n_active"], b["dWg_c"], b["dWu_c"], b["dWd_c"], self.ws, stream)
         if self.overlap:
             self._join(main)
         elif self.S:

@@ -261,8 +261,10 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   // pair 0, then all of pair 1), and how many bytes of valid data follow the tile origins.
   constexpr int64_t es = sizeof(T);
   const int64_t b_tile = (int64_t)t.group * p.b_group + (B_KC ? (int64_t)n0 * p.ldb : (int64_t)n0);
-  const int64_t a_tile = (int64_t)a_row0 * p.lda;
-  const int64_t a_end = ((int64_t)(rows - 1) * p.lda + p.K) * es;
+  // gathered A: the operand pointer stays at the origin of the whole matrix and the row map names the rows
+  const RowMap amap = {p.a_index, p.a_index ? p.a_index_div : 1, a_row0, rows};
+  const int64_t a_tile = p.a_index ? 0 : (int64_t)a_row0 * p.lda;
+  const int64_t a_end = ((int64_t)((p.a_index ? p.a_src_rows : rows) - 1) * p.lda + p.K) * es;
   const int64_t b_end = B_KC ? ((int64_t)(n_valid - 1) * p.ldb + p.K) * es : ((int64_t)(p.K - 1) * p.ldb + (p.N - n0)) * es;
   auto segf = [&](int sg) __attribute__((always_inline)) {
     SegSrc<T, NB> s;
@@ -320,8 +322,9 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       float z[W], dz[W];
       if (aux) Pack<T, W>::widen(aux->r[0], z);
       else Pack<T, W>::load((const T*)p.in[0] + off, z);
+      const float sc = p.c_scale ? p.c_scale[p.a_index[a_row0 + m]] : 1.f;
 #pragma unroll
-      for (int q = 0; q < W; q++) dz[q] = v[0][q] * gelu_grad_f<T>(z[q]);
+      for (int q = 0; q < W; q++) dz[q] = sc * v[0][q] * gelu_grad_f<T>(z[q]);
       Pack<T, W>::store((T*)p.out[0] + off, dz);
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[W];
@@ -339,11 +342,13 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
         Pack<T, W>::load((const T*)p.in[0] + off, g);
         Pack<T, W>::load((const T*)p.in[1] + off, u);
       }
+      const float sc = p.c_scale ? p.c_scale[p.a_index[a_row0 + m]] : 1.f;
 #pragma unroll
       for (int q = 0; q < W; q++) {
         const float s = sigmoidf_<T>(g[q]);
-        du[q] = v[0][q] * g[q] * s;
-        dg[q] = v[0][q] * u[q] * s * (1.f + g[q] * (1.f - s));
+        const float dh = sc * v[0][q];
+        du[q] = dh * g[q] * s;
+        dg[q] = dh * u[q] * s * (1.f + g[q] * (1.f - s));
       }
       Pack<T, W>::store((T*)p.out[0] + off, dg);
       Pack<T, W>::store((T*)p.out[1] + off, du);
@@ -351,10 +356,10 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
   };
   if constexpr (kAuxLoads > 0) {
     EpiWithAux<decltype(body), decltype(pre), Aux, kAuxLoads> epi{body, pre};
-    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
+    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi, amap);
   } else {
     auto epi = [&](int m, int n, const auto& v) __attribute__((always_inline)) { body(m, n, v, (const Aux*)nullptr); };
-    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi);
+    Core::run(smem, p.n_pairs * p.n_segs, nk, segf, p.lda, p.ldb, rows, n_valid, epi, amap);
   }
 }
 
@@ -459,7 +464,7 @@ __global__ __launch_bounds__(Core::NT) void w_gemm_kernel(WGemm p) {
     if (NB == 2) Pack<T, W>::store_nt((T*)p.C[1] + off, v[NB - 1]);
   };
   MOE_TRACE_BEGIN();
-  Core::run(smem, 1, (K + BK - 1) / BK, segf, p.lda, p.ldb, m_valid, n_valid, epi);
+  Core::run(smem, 1, (K + BK - 1) / BK, segf, p.lda, p.ldb, m_valid, n_valid, epi, RowMap{nullptr, 1, 0, 0});
   MOE_TRACE_W_TILE(0x1000 | NB | (BM << 4), g, min(K, 0xffff) << 16);
   }
 }
@@ -568,6 +573,10 @@ struct FwdArgs {
   const void *Xin, *Wg, *Wu, *Wd;
   void *G, *U, *H, *Yout;
   void* ws;
+  // gathered input (moe_expert_fwd_gather): Xin is the token matrix [src_rows, d] and grouped row r reads
+  // its row src_of[r] / src_div
+  const int32_t* src_of = nullptr;
+  int src_div = 1, src_rows = 0;
 };
 
 template <int PATH>
@@ -585,6 +594,7 @@ static void expert_fwd_impl(const FwdArgs& a, hipStream_t st) {
   p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
   p.N = a.F; p.K = a.d; p.n_pairs = 1; p.n_segs = 1;
   p.A[0] = a.Xin; p.lda = a.d; p.a_seg = 0; p.a_rows_out = 0;
+  p.a_index = a.src_of; p.a_index_div = a.src_div; p.a_src_rows = a.src_rows;
   p.B[0] = a.Wg; p.Bdual = a.Wu; p.ldb = a.F; p.b_group = (int64_t)a.d * a.F; p.b_seg = 0;
   p.out[0] = a.G; p.out[1] = a.U; p.out[2] = a.H; p.ldc = a.F; p.c_rows_out = 1;
   if (a.Wu) launch_row<RowCores<PATH, 2, false>, 2, EPI_SWIGLU_FWD, false>("gemm_fwd_gate_up", p, max_tiles, st);
@@ -613,6 +623,12 @@ struct BwdArgs {
   void *dWg, *dWu, *dWd;
   void* ws;
   size_t plan_sz;
+  // gathered upstream gradient (moe_expert_bwd_gather): the product dH reads row src_of[r] / src_div of
+  // dY [src_rows, d] and scales row r by row_w[src_of[r]]; the weight gradient of Wd still reads dYin
+  const void* dY = nullptr;
+  const int32_t* src_of = nullptr;
+  const float* row_w = nullptr;
+  int src_div = 1, src_rows = 0;
 };
 
 template <int PATH>
@@ -635,6 +651,9 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
   p.tiles = pl.tiles; p.n_tiles = pl.n_tiles; p.n_rows = a.n_rows;
   p.N = a.F; p.K = a.d; p.n_pairs = 1; p.n_segs = 1;
   p.A[0] = a.dYin; p.lda = a.d; p.a_rows_out = 0;
+  if (a.src_of) {
+    p.A[0] = a.dY; p.a_index = a.src_of; p.a_index_div = a.src_div; p.a_src_rows = a.src_rows; p.c_scale = a.row_w;
+  }
   p.B[0] = a.Wd; p.ldb = a.d; p.b_group = (int64_t)a.F * a.d;
   p.in[0] = a.G; p.in[1] = a.U; p.out[0] = dG; p.out[1] = dU; p.ldc = a.F; p.c_rows_out = 1;
   const bool gated = a.Wu != nullptr;  // two-matrix expert otherwise: dG is dZ, no dU
@@ -676,7 +695,7 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       WGemm wl_ = w, vl_ = v;
       wl_.k_min = vl_.k_min = 1;
       wl_.k_max = vl_.k_max = kLightGroupRows;
-      wl_.n_reps = vl_.n_reps = kLightReps;
+      wl_.n_reps = vl_.n_reps = MOE_KNOB("MOE_LIGHT_REPS", kLightReps);
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
       if (gated) launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
       else launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwgu", v, a.n_groups, st);
@@ -788,6 +807,84 @@ extern "C" int moe_expert_bwd(const moe_shape_t* shape, int32_t n_groups, const 
     default: expert_bwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
   }
   return launch_status("moe_expert_bwd");
+}
+
+// The same two calls reading token rows in place (grouped mode only): see include/moe_hip.h.
+extern "C" int moe_expert_fwd_gather(const moe_shape_t* shape, const int32_t* offsets, const int32_t* src_of,
+                                     const void* X, const void* Wg, const void* Wu, const void* Wd, void* G, void* U,
+                                     void* H, void* Yout, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_expert_fwd_gather");
+  if (rc) return rc;
+  const int n_groups = shape->E, n_rows = shape->T * shape->k;
+  if (!offsets || !Wg || !Wd || !ws || (n_rows > 0 && (!src_of || !X || !G || (Wu && !U) || !H || !Yout))) {
+    set_error("moe_expert_fwd_gather: null pointer");
+    return MOE_EINVAL;
+  }
+  const void* ptrs[] = {X, Wg, Wu, Wd, G, U, H, Yout, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) {
+      set_error("moe_expert_fwd_gather: every tensor must be 16-byte aligned");
+      return MOE_EINVAL;
+    }
+  if ((int64_t)shape->T * shape->d * (int64_t)elem_size(shape->dtype) >= ((int64_t)1 << 32) - 4096) {
+    set_error("moe_expert_fwd_gather: X must be smaller than 4 GiB (32-bit byte offsets); use moe_expert_fwd on a permuted copy");
+    return MOE_EINVAL;
+  }
+  const size_t need = moe_expert_fwd_workspace_bytes(shape, n_groups, n_rows, 0);
+  if (ws_bytes < need) {
+    set_error("moe_expert_fwd_gather: workspace of %zu bytes, need %zu", ws_bytes, need);
+    return MOE_EWS;
+  }
+  if (n_rows == 0) return MOE_OK;
+  FwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, X, Wg, Wu, Wd, G, U, H, Yout, ws};
+  a.src_of = src_of; a.src_div = shape->k; a.src_rows = shape->T;
+  switch (pick_path(shape)) {
+    case PATH_F32: expert_fwd_impl<PATH_F32>(a, (hipStream_t)stream); break;
+    case PATH_BF16: expert_fwd_impl<PATH_BF16>(a, (hipStream_t)stream); break;
+    default: expert_fwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
+  }
+  return launch_status("moe_expert_fwd_gather");
+}
+
+extern "C" int moe_expert_bwd_gather(const moe_shape_t* shape, const int32_t* offsets, const int32_t* src_of,
+                                     const void* Xp, const void* Wg, const void* Wu, const void* Wd, const void* G,
+                                     const void* U, const void* H, const void* dY, const float* topk_w, const void* dYp,
+                                     void* dXp, int32_t* active_ids, int32_t* n_active, void* dWg_c, void* dWu_c,
+                                     void* dWd_c, void* ws, size_t ws_bytes, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_expert_bwd_gather");
+  if (rc) return rc;
+  const int n_groups = shape->E, n_rows = shape->T * shape->k;
+  if (!offsets || !Wg || !Wd || !ws || !active_ids || !n_active || !dWg_c || (Wu && !dWu_c) || !dWd_c ||
+      (n_rows > 0 && (!src_of || !Xp || !G || (Wu && !U) || !H || !dY || !topk_w || !dYp || !dXp))) {
+    set_error("moe_expert_bwd_gather: null pointer");
+    return MOE_EINVAL;
+  }
+  const void* ptrs[] = {Xp, Wg, Wu, Wd, G, U, H, dY, dYp, dXp, dWg_c, dWu_c, dWd_c, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) {
+      set_error("moe_expert_bwd_gather: every tensor must be 16-byte aligned");
+      return MOE_EINVAL;
+    }
+  if ((int64_t)shape->T * shape->d * (int64_t)elem_size(shape->dtype) >= ((int64_t)1 << 32) - 4096) {
+    set_error("moe_expert_bwd_gather: dY must be smaller than 4 GiB (32-bit byte offsets); use moe_expert_bwd");
+    return MOE_EINVAL;
+  }
+  const size_t need = moe_expert_bwd_workspace_bytes(shape, n_groups, n_rows, 0);
+  if (ws_bytes < need) {
+    set_error("moe_expert_bwd_gather: workspace of %zu bytes, need %zu", ws_bytes, need);
+    return MOE_EWS;
+  }
+  BwdArgs a = {shape->d, shape->d_ff, n_groups, n_rows, offsets, Xp, Wg, Wu, Wd, G, U, H, dYp, dXp,
+               active_ids, n_active, dWg_c, dWu_c, dWd_c, ws, plan_size_for(n_groups, n_rows, false)};
+  a.dY = dY; a.src_of = src_of; a.row_w = topk_w; a.src_div = shape->k; a.src_rows = shape->T;
+  switch (pick_path(shape)) {
+    case PATH_F32: expert_bwd_impl<PATH_F32>(a, (hipStream_t)stream); break;
+    case PATH_BF16: expert_bwd_impl<PATH_BF16>(a, (hipStream_t)stream); break;
+    default: expert_bwd_impl<PATH_BF16_DMA>(a, (hipStream_t)stream); break;
+  }
+  return launch_status("moe_expert_bwd_gather");
 }
 
 // ------------------------------------------------------------------------------------ router

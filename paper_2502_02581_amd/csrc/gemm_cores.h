@@ -33,6 +33,17 @@ struct SegSrc {
   int64_t a_bytes, b_bytes;
 };
 
+// Where row m of the A tile lives.  Plain tiles: row m of the tile (the tile origin is part of the
+// operand pointers).  Gathered tiles (K-contiguous A only): row idx[row0 + m] / div of the whole
+// operand, whose origin the pointers then are -- the token rows of X or dY read in grouped order
+// without a permuted copy.
+struct RowMap {
+  const int32_t* idx;  // NULL: plain
+  int32_t div, row0, rows;  // rows: valid rows of the tile (rows at or beyond read as zero)
+  __device__ __forceinline__ bool gathered() const { return idx != nullptr; }
+  __device__ __forceinline__ int64_t operator()(int m) const { return idx ? (int64_t)(idx[row0 + m] / div) : (int64_t)m; }
+};
+
 // What one K iteration reads, for the cores that address element by element.
 template <typename T, int NB>
 struct IterSrc {
@@ -62,7 +73,7 @@ struct F32Core {
 
   template <class SegFn, class Epi>
   __device__ static void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb, int m_valid,
-                             int n_valid, Epi epi) {
+                             int n_valid, Epi epi, const RowMap& amap) {
     const int n_iters = n_segs * nk;
     auto src = [&](int it) { return iter_src<float, NB, A_KC, B_KC>(segf, it, nk, BK, lda, ldb); };
     float* As = (float*)smem;            // [BK][LD]  (k major)
@@ -83,7 +94,7 @@ struct F32Core {
         int m, k;
         if (A_KC) { m = idx / BK; k = idx % BK; } else { k = idx / BM; m = idx % BM; }
         float v = 0.f;
-        if (m < m_valid && k < s.k_left) v = A_KC ? s.a[(int64_t)m * lda + k] : s.a[(int64_t)k * lda + m];
+        if (m < m_valid && k < s.k_left) v = A_KC ? s.a[amap(m) * lda + k] : s.a[(int64_t)k * lda + m];
         As[k * LD + m] = v;
       }
 #pragma unroll
@@ -157,7 +168,7 @@ struct MfmaCore {
   // ---- global -> registers (16 bytes per access), zero outside the valid extents
   template <int ROWS, int NVEC, bool KC>
   __device__ static __forceinline__ void gload(const bf16_t* base, int64_t ld, int rows_valid, int k_left,
-                                               uint4 (&r)[NVEC]) {
+                                               uint4 (&r)[NVEC], const RowMap& map) {
 #pragma unroll
     for (int i = 0; i < NVEC; i++) {
       const int v = threadIdx.x + i * NT;
@@ -165,8 +176,11 @@ struct MfmaCore {
       if (KC) { row = v / (BK / 8); kk = (v % (BK / 8)) * 8; }
       else { kk = v / (ROWS / 8); row = (v % (ROWS / 8)) * 8; }
       const bool ok = row < rows_valid && kk < k_left && (ROWS * BK / 8 % NT == 0 || v < ROWS * BK / 8);
-      const bf16_t* p = KC ? base + (int64_t)row * ld + kk : base + (int64_t)kk * ld + row;
-      r[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+      r[i] = make_uint4(0, 0, 0, 0);
+      if (ok) {
+        const bf16_t* p = KC ? base + (map.gathered() ? map(row) : (int64_t)row) * ld + kk : base + (int64_t)kk * ld + row;
+        r[i] = *reinterpret_cast<const uint4*>(p);
+      }
     }
   }
   // ---- registers -> LDS
@@ -237,9 +251,10 @@ struct MfmaCore {
 
   template <class SegFn, class Epi>
   __device__ static void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb, int m_valid,
-                             int n_valid, Epi epi) {
+                             int n_valid, Epi epi, const RowMap& amap) {
     const int n_iters = n_segs * nk;
     auto src = [&](int it) { return iter_src<bf16_t, NB, A_KC, B_KC>(segf, it, nk, BK, lda, ldb); };
+    const RowMap plain = {nullptr, 1, 0, 0};
     bf16_t* lds = (bf16_t*)smem;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm0 = (wave / WN) * (BM / WM), wn0 = (wave % WN) * (BN / WN);
@@ -257,9 +272,9 @@ struct MfmaCore {
     uint4 ra[A_VEC], rb[NB][B_VEC];
     auto fetch = [&](int it) {
       IterSrc<bf16_t, NB> s = src(it);
-      gload<BM, A_VEC, A_KC>(s.a, lda, m_valid, s.k_left, ra);
+      gload<BM, A_VEC, A_KC>(s.a, lda, m_valid, s.k_left, ra, amap);
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) gload<BN, B_VEC, B_KC>(s.b[nb], ldb, n_valid, s.k_left, rb[nb]);
+      for (int nb = 0; nb < NB; nb++) gload<BN, B_VEC, B_KC>(s.b[nb], ldb, n_valid, s.k_left, rb[nb], plain);
     };
     auto stash = [&](int stage) {
       bf16_t* As = lds + stage * STAGE_ELEMS;
@@ -560,7 +575,7 @@ struct MfmaDmaCore {
   // (the valid extents are not needed here: the descriptors' byte counts zero-fill the loads and the
   // epilogue functor masks the stores)
   __device__ static __forceinline__ void run(char* smem, int n_segs, int nk, SegFn segf, int64_t lda, int64_t ldb,
-                                             int /*m_valid*/, int /*n_valid*/, Epi epi) {
+                                             int /*m_valid*/, int /*n_valid*/, Epi epi, const RowMap& amap) {
     const int n_iters = n_segs * nk;
     MOE_PHASE(0);
     bf16_t* lds = (bf16_t*)smem;
@@ -597,6 +612,19 @@ struct MfmaDmaCore {
 #pragma unroll
     for (int j = 0; j < A_NI; j++)
       voa[j] = piece_offset<BM, A_KC>(wave, lane, (uint32_t)lda) + (uint32_t)(j * load_stride<BM, A_KC>()) * (uint32_t)lda * 2u;
+    if constexpr (A_KC) {
+      // gathered A rows: the same pieces, from the rows the map names.  The descriptor then spans the
+      // whole operand, so the rows beyond the tile's valid ones get an offset no descriptor reaches
+      // (they read as zero, as they do past the end of a plain tile).
+      if (amap.gathered()) {
+        const int q = wave * 64 + lane, row = q / PR_KC, c = (q % PR_KC) ^ kc_swizzle(row);
+#pragma unroll
+        for (int j = 0; j < A_NI; j++) {
+          const int r = row + j * load_stride<BM, A_KC>();
+          voa[j] = r < amap.rows ? (uint32_t)amap(r) * (uint32_t)lda * 2u + (uint32_t)c * 16u : 0xffffff00u;
+        }
+      }
+    }
 #pragma unroll
     for (int j = 0; j < B_NI; j++)
       vob[j] = piece_offset<BN, B_KC>(wave, lane, (uint32_t)ldb) + (uint32_t)(j * load_stride<BN, B_KC>()) * (uint32_t)ldb * 2u;

@@ -53,12 +53,18 @@ struct RowGemm {
   const void* A[2];         // per pair; element (row, k) at A + seg*a_seg + row*lda + k
   int64_t lda, a_seg;
   int32_t a_rows_out;       // A rows are indexed by row0_out (saved activations) instead of row0_in
+  // gathered A (pair 0, single segment, K-contiguous A only): row r of the call reads row
+  // a_index[r] / a_index_div of A, which has a_src_rows rows (NULL: A is indexed by r itself)
+  const int32_t* a_index;
+  int32_t a_index_div, a_src_rows;
   const void* B[2];         // per pair; + group*b_group + seg*b_seg
   const void* Bdual;        // second B of a dual GEMM (pair 0 only)
   int64_t ldb, b_group, b_seg;
   // epilogue
   void* out[3];
   const void* in[2];
+  // activation-backward epilogues: row r of the product is scaled by c_scale[a_index[r]] first (NULL: 1)
+  const float* c_scale;
   int64_t ldc;
   int32_t c_rows_out;       // outputs indexed by row0_out
 };

@@ -32,6 +32,15 @@ struct ProfScope {
   }
 };
 
+// Tuning knobs: compile-time constants in the library that ships; a development build (-DMOE_TUNE)
+// reads them from the environment at every launch instead, so that one build serves a sweep.
+#ifdef MOE_TUNE
+int tune_knob(const char* name, int dflt);
+#define MOE_KNOB(name, dflt) moe::tune_knob(name, dflt)
+#else
+#define MOE_KNOB(name, dflt) (dflt)
+#endif
+
 inline size_t elem_size(int dtype) { return dtype == MOE_F32 ? 4 : 2; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -37,7 +37,7 @@ class OnDevice:
         return self.w[int(e)].float().cpu().numpy()
 
 
-def run_full(cfg):
+def run_full(cfg, gather=False):
     import paper_2502_02581_amd as moe
 
     dev = "cuda:0"
@@ -45,7 +45,7 @@ def run_full(cfg):
     W = wl.make_weights(cfg, dev)
     g = {k: v.to(dev) for k, v in inp.items()}
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
-    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, aux_alpha=cfg.aux_alpha)
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, aux_alpha=cfg.aux_alpha, gather=gather)
     sh = [W.get("Wsg"), W.get("Wsu"), W.get("Wsd")]
     hp.forward(g["logits"], g["X"], W["Wg"], W.get("Wu"), W["Wd"], *sh)
     hp.backward(g["dY"], g["X"], W["Wg"], W.get("Wu"), W["Wd"], *sh)
@@ -53,10 +53,11 @@ def run_full(cfg):
     return inp, W, hp
 
 
-@pytest.mark.parametrize("name", ["qwen", "phi", "dsv3", "stress", "gpt-s", "gpt-l"])
-def test_full_size_sampled(name):
+@pytest.mark.parametrize("name,gather", [("qwen", False), ("phi", False), ("dsv3", False), ("stress", False),
+                                         ("gpt-s", False), ("gpt-l", False), ("dsv3", True), ("stress", True)])
+def test_full_size_sampled(name, gather):
     cfg = wl.CONFIGS[name]
-    inp, W, hp = run_full(cfg)
+    inp, W, hp = run_full(cfg, gather)
     b = hp.b
     lg = inp["logits"].numpy()
     # ---- integers and weights, in full
