@@ -227,8 +227,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="dsv3", choices=list(wl.CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--overlap-shared", action="store_true",
-                    help="run the shared experts on a second stream (per-kernel durations then overlap)")
+    ap.add_argument("--no-overlap-shared", action="store_true",
+                    help="keep the shared experts on the main stream in the timed region too (default: second stream)")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every kernel of the timed steps from the host (default: one captured HIP graph per step)")
     ap.add_argument("--gather", action="store_true",
                     help="routed experts read X and dY in place through src_of (moe_expert_*_gather)")
     args = ap.parse_args()
@@ -249,7 +251,7 @@ def main():
     weights = wl.make_weights(cfg, dev)
     g = {k: v.to(dev) for k, v in inp.items()}
     shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
-    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, overlap_shared=args.overlap_shared,
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, dev, overlap_shared=not args.no_overlap_shared,
                         aux_alpha=cfg.aux_alpha, gather=args.gather)
     sh = [weights.get("Wsg"), weights.get("Wsu"), weights.get("Wsd")]
 
@@ -262,13 +264,24 @@ def main():
     torch.cuda.synchronize()
     sampled_err = verify(cfg, inp, weights, hp)
     # ---- the timed region: exactly `steps` bare steps (no per-kernel events), wall clock around all of
-    # them, and one pair of HIP events per step on the launch stream for the median
+    # them, and one pair of HIP events per step on the launch stream for the median.  A step is the
+    # same ~40 launches every time, so it is captured once into a HIP graph and replayed (the small
+    # workloads are otherwise bound by the host's launch rate); the shared experts run on a second stream.
+    run = step
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
+        sampled_err = max(sampled_err, verify(cfg, inp, weights, hp))   # the replayed step, checked as well
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for a, b in ev:
         a.record()
-        step()
+        run()
         b.record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -277,6 +290,7 @@ def main():
 
     # ---- a second, profiled pass of the same steps: the library brackets every launch with HIP events on
     # the launch stream (this costs a little time per launch, which is why it is not the headline)
+    hp.overlap = False   # serial launches: the per-kernel durations then do not overlap
     moe.moe_profile_enable(True)
     t0p = time.perf_counter()
     for _ in range(args.steps):
@@ -299,12 +313,13 @@ def main():
     moe.moe_profile_enable(False)
     # cold-cache variant (outside the timed region, reported beside `value`): L2 and the infinity cache are
     # overwritten before every step by filling the 2 GiB probe buffer, and each step is timed on its own
+    hp.overlap = bool(cfg.n_shared) and not args.no_overlap_shared
     cold = []
     for _ in range(COLD_STEPS):
         probe.fill_(2)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        step()
+        run()
         torch.cuda.synchronize()
         cold.append(time.perf_counter() - t1)
     del probe
@@ -353,6 +368,8 @@ def main():
         "metric": "moe_layer_fwd_bwd_tokens_per_s", "value": round(cfg.T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "median_step_ms": round(median_ms, 4), "profiled_pass_ms_per_step": round(dt_prof / args.steps * 1e3, 4),
+        "launch": {"hip_graph": not args.no_graph, "shared_experts_on_second_stream": bool(cfg.n_shared) and not args.no_overlap_shared,
+                   "profiled_pass": "host launches, one stream, HIP events around every kernel"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} top-{cfg.k} {cfg.gate} d_ff={cfg.d_ff} "

@@ -533,3 +533,42 @@ def test_nothing_outside_the_outputs_is_written(cfg):
     # and the result is still the right one
     ref = run_oracle(cfg, p)
     compare_layer(cfg, {k: v.cpu() for k, v in hp.b.items()}, ref)
+
+
+def test_step_replayed_from_a_hip_graph():
+    """One forward+backward captured into a HIP graph (the shared experts on a second stream, as the
+    benchmark launches it) and replayed several times, with eager steps on other inputs and
+    synchronisations in between: every replay must reproduce the eager result bit for bit."""
+    import paper_2502_02581_amd as moe
+
+    cfg = small_cfg("graph", T=620, d=128, E=12, k=3, d_ff=192, dtype="bf16", zipf_s=1.3, gate="sigmoid", n_shared=1,
+                    d_ff_shared=128, aux_alpha=0.001)
+    p = problem(cfg, unit_scale=True)
+    shape = moe.MoEShape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.d_ff, cfg.dtype, cfg.gate, cfg.renorm)
+    hp = moe.MoEHotPath(shape, cfg.n_shared, cfg.d_ff_shared, overlap_shared=True, aux_alpha=cfg.aux_alpha)
+    g = {k: v.to(hp.device) for k, v in p.items()}
+    other = {k: (v.clone().normal_() if v.is_floating_point() else v) for k, v in g.items()}
+    sh = lambda q: [q.get("Wsg"), q.get("Wsu"), q.get("Wsd")]
+
+    def step(q):
+        hp.forward(q["logits"], q["X"], q["Wg"], q.get("Wu"), q["Wd"], *sh(q))
+        hp.backward(q["dY"], q["X"], q["Wg"], q.get("Wu"), q["Wd"], *sh(q))
+
+    keys = ("topk_idx", "row_of", "Y", "dX", "dw", "dlogits", "dWg_c", "dWd_c", "dWsg", "aux_loss")
+    step(g)
+    torch.cuda.synchronize()
+    eager = {k: hp.b[k].clone() for k in keys}
+    n_act = int(hp.b["n_active"].item())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(g)
+    for rep in range(4):
+        step(other)                      # eager work of the program itself between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in keys:
+            a, b = hp.b[k], eager[k]
+            if k in ("dWg_c", "dWd_c"):
+                a, b = a[:n_act], b[:n_act]
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, k)
