@@ -695,7 +695,16 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
       WGemm wl_ = w, vl_ = v;
       wl_.k_min = vl_.k_min = 1;
       wl_.k_max = vl_.k_max = kLightGroupRows;
-      wl_.n_reps = vl_.n_reps = MOE_KNOB("MOE_LIGHT_REPS", kLightReps);
+      // column tiles per block: at most kLightReps, and the same for every block of a row of tiles (11
+      // column tiles go 6 + 5, not 8 + 3: consecutive blocks run on different XCDs, and unequal blocks
+      // would load the XCDs unequally)
+      const int reps_max = MOE_KNOB("MOE_LIGHT_REPS", kLightReps);
+      auto even_reps = [&](int n_cols) {
+        const int ntn = ceil_div(n_cols, C::template core_light<1>::BN);
+        return ceil_div(ntn, ceil_div(ntn, reps_max));
+      };
+      wl_.n_reps = even_reps(wl_.N);
+      vl_.n_reps = even_reps(vl_.N);
       launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwd", w, a.n_groups, st);
       if (gated) launch_w<typename C::template core<2, false, false>, 2>("gemm_bwd_dwgu", v, a.n_groups, st);
       else launch_w<typename C::template core<1, false, false>, 1>("gemm_bwd_dwgu", v, a.n_groups, st);

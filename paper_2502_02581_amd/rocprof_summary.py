@@ -31,7 +31,8 @@ def stats(args):
     rows = list(csv.DictReader(open(args.csv)))
     with open(args.out, "w") as f:
         f.write("# rocprofv3 --kernel-trace --stats summary\n\nCommand (run from the repo root on one MI355X):\n\n")
-        f.write(f"    {args.cmd}\n\nCalls include the warm-up steps. Durations in microseconds.\n\n")
+        f.write(f"    {args.cmd}\n\nKernels of commit {args.commit}.  Calls include the warm-up steps and the profiled pass "
+                "(every step runs twice: timed, then with the library's own events). Durations in microseconds.\n\n")
         f.write("| kernel | calls | total us | avg us | min us | max us | % |\n|---|---|---|---|---|---|---|\n")
         for r in rows:
             if float(r["Percentage"]) < 0.01:
@@ -62,6 +63,7 @@ def traffic(args):
     with open(args.out, "w") as f:
         f.write("# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE\n#\n")
         f.write(f"# Command (run twice, once per counter, from the repo root on one MI355X):\n#     {args.cmd}\n#\n")
+        f.write(f"# commit: {args.commit}\n#\n")
         f.write(f"# copy_probe_kernel moves {args.probe_bytes} bytes each way: FETCH_SIZE reads {fetch[probe[0]][0]:.1f}, "
                 f"WRITE_SIZE reads {write[probe[0]][0]:.1f}\n")
         f.write(f"# scale: {f_fac:.2f} bytes per FETCH_SIZE unit, {w_fac:.2f} bytes per WRITE_SIZE unit (nominal unit: 1 KiB)\n")
@@ -87,6 +89,7 @@ def counters(args):
         f.write("# rocprofv3 --pmc counter sums per kernel (all dispatches of the run)\n\nCommands (from the repo root on one MI355X):\n\n")
         for c in args.cmd:
             f.write(f"    {c}\n")
+        f.write(f"\nKernels of commit {args.commit}.\n")
         f.write("\nDerived: MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES); executed bf16 MFMA FLOPs = "
                 "512 x SQ_INSTS_VALU_MFMA_MOPS_BF16 (padding rows of ragged tiles included); LDS bank conflict share = "
                 "SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE; LDS wait share = SQ_WAIT_INST_LDS / SQ_WAVE_CYCLES.\n\n")
@@ -126,6 +129,7 @@ def main():
     s.add_argument("csv")
     s.add_argument("out")
     s.add_argument("--cmd", required=True)
+    s.add_argument("--commit", default="not recorded")
     s.set_defaults(fn=stats)
     t = sub.add_parser("traffic")
     t.add_argument("fetch_csv")
@@ -133,11 +137,13 @@ def main():
     t.add_argument("out")
     t.add_argument("--probe-bytes", type=int, required=True)
     t.add_argument("--cmd", required=True)
+    t.add_argument("--commit", default="not recorded")
     t.set_defaults(fn=traffic)
     c = sub.add_parser("counters")
     c.add_argument("out")
     c.add_argument("csv", nargs="+")
     c.add_argument("--cmd", action="append", required=True)
+    c.add_argument("--commit", default="not recorded")
     c.set_defaults(fn=counters)
     args = ap.parse_args()
     args.fn(args)

@@ -25,7 +25,7 @@ def test_traffic_scaled_by_copy_probe(tmp_path):
     out = tmp_path / "t.txt"
 
     class A:
-        fetch_csv, write_csv, probe_bytes, cmd = str(fetch), str(write), 1000, "cmd"
+        fetch_csv, write_csv, probe_bytes, cmd, commit = str(fetch), str(write), 1000, "cmd", "abc1234"
 
     A.out = str(out)
     rs.traffic(A)
@@ -35,6 +35,7 @@ def test_traffic_scaled_by_copy_probe(tmp_path):
     assert got[name] == 4200.0
     assert got[probe.replace("void moe::", "moe::")] == 2000.0
     assert not any("at::native" in k for k in got)
+    assert "# commit: abc1234" in out.read_text()
 
 
 def test_counters_ratios(tmp_path):
@@ -46,7 +47,7 @@ def test_counters_ratios(tmp_path):
     out = tmp_path / "c.md"
 
     class A:
-        csv, cmd = [str(c)], ["cmd one"]
+        csv, cmd, commit = [str(c)], ["cmd one"], "abc1234"
 
     A.out = str(out)
     rs.counters(A)
