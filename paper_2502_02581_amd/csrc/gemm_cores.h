@@ -537,6 +537,13 @@ struct MfmaDmaCore {
       c.ad = make_desc(g.a, c.a_rem);
 #pragma unroll
       for (int nb = 0; nb < NB; nb++) c.bd[nb] = make_desc(g.b[nb], c.b_rem);
+      // The words above come out of v_readfirstlane.  Five wait states must pass before a tile load reads
+      // them, wherever the compiler places that load (a segment starts once or twice per tile, so this
+      // costs nothing); the statements are tied to the descriptors and keep their order, so the wait
+      // stands behind the last of those writes.
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) asm volatile("" : "+s"(c.bd[nb]) : : "memory");
+      asm volatile("s_nop 4" : "+s"(c.ad) : : "memory");
       c.a_step = A_KC ? (int64_t)BK * 2 : (int64_t)BK * 2 * lda;
       c.b_step = B_KC ? (int64_t)BK * 2 : (int64_t)BK * 2 * ldb;
       c.k_left = g.k_len;

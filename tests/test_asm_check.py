@@ -36,6 +36,26 @@ def test_enough_wait_states_or_other_registers_pass():
     assert asm_check.check_descriptor_hazards(ok) == []
 
 
+def test_writers_on_other_paths_are_found():
+    # the writer sits at the tail of the loop, below the load in the file: it precedes the load through the back edge
+    loop = _asm(".LBB0_1:", "\ts_mov_b32 m0, s3", "\ts_nop 0", LOAD, "\tv_mfma_f32_32x32x16_bf16 a[0:15], v[0:3], v[4:7], a[0:15]",
+                "\tv_readfirstlane_b32 s5, v9", "\ts_cbranch_scc1 .LBB0_1")
+    found = asm_check.check_descriptor_hazards(loop)
+    assert len(found) == 1 and "s[5]" in found[0] and "3 wait states" in found[0]
+    # the writer sits in the arm of an `if` that jumps over the other arm to the load
+    arm = _asm("\ts_cbranch_scc0 .LBB0_2", "\tv_readfirstlane_b32 s7, v9", "\ts_branch .LBB0_3", ".LBB0_2:",
+               "\ts_mov_b32 s7, 0", "\ts_nop 7", ".LBB0_3:", "\ts_mov_b32 m0, s3", "\ts_nop 0", LOAD)
+    found = asm_check.check_descriptor_hazards(arm)
+    assert len(found) == 1 and "s[7]" in found[0]
+    # the same with enough wait states behind the writer on that path
+    arm[2:3] = ["\tv_readfirstlane_b32 s7, v9", "\ts_nop 4"]
+    assert asm_check.check_descriptor_hazards(arm) == []
+    # a path that ends before the load: what stands right above the load in the file but never runs into it is no writer
+    dead = _asm("\ts_cbranch_scc1 .LBB0_5", "\tv_readfirstlane_b32 s4, v1", "\ts_endpgm", ".LBB0_5:", "\ts_mov_b32 m0, s3",
+                "\ts_nop 0", LOAD)
+    assert asm_check.check_descriptor_hazards(dead) == []
+
+
 def test_scratch_in_a_gemm_kernel_is_flagged():
     lines = ["_ZN3moe15row_gemm_kernelIxEEv:", "\ts_endpgm", "; ScratchSize: 1088",
              "_ZN3moe12route_kernelIxEEv:", "\ts_endpgm", "; ScratchSize: 16"]
