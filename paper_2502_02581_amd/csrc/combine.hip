@@ -1,6 +1,9 @@
 // moe_combine / moe_combine_bwd: the weighted sum of Eq. 3 and its adjoint.
 // One block per token; every lane owns 16-byte pieces of the row, accumulates the k
 // gathered rows in fp32 and rounds once.  Pure HBM streaming: (k + 1 [+1]) rows in, 1 row out.
+// The gathered rows are read exactly once, so their loads carry the streaming hint (without it the
+// k*T rows displace each other and the token rows in the caches: 0.46 -> 0.40 ms per step for the
+// two combine launches of the DeepSeek-shaped workload).
 #include "moe_common.h"
 
 namespace moe {
@@ -28,7 +31,7 @@ __global__ __launch_bounds__(512) void combine_kernel(const T* __restrict__ Yp,
     for (int c = threadIdx.x; c < vec_per_row; c += blockDim.x) {
       float v[KM][N], acc[N];
 #pragma unroll
-      for (int j = 0; j < KM; j++) Vec16<T>::load(src[j] + c * N, v[j]);
+      for (int j = 0; j < KM; j++) Vec16<T>::load_nt(src[j] + c * N, v[j]);
       if (Yadd) {
         Vec16<T>::load(Yadd + (size_t)t * d + c * N, acc);
       } else {
@@ -91,7 +94,7 @@ __global__ __launch_bounds__(512) void combine_bwd_kernel(const T* __restrict__ 
       float g[N], y[KM][N];
       Vec16<T>::load(dY + (size_t)t * d + c * N, g);
 #pragma unroll
-      for (int j = 0; j < KM; j++) Vec16<T>::load(Yp + row[j] + c * N, y[j]);
+      for (int j = 0; j < KM; j++) Vec16<T>::load_nt(Yp + row[j] + c * N, y[j]);
 #pragma unroll
       for (int j = 0; j < KM; j++) {
         float o[N];

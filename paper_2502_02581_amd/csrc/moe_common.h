@@ -82,6 +82,7 @@ template <> struct Elem<bf16_t> {
 template <typename T> struct Vec16;
 template <> struct Vec16<float> {
   static constexpr int N = 4;
+  __device__ static __forceinline__ void load_nt(const float* p, float (&o)[4]) { load(p, o); }
   __device__ static __forceinline__ void load(const float* p, float (&o)[4]) {
     float4 v = *reinterpret_cast<const float4*>(p);
     o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
@@ -92,6 +93,16 @@ template <> struct Vec16<float> {
 };
 template <> struct Vec16<bf16_t> {
   static constexpr int N = 8;
+  // the same load with a streaming hint: for rows that nothing on the chip reads again soon
+  __device__ static __forceinline__ void load_nt(const bf16_t* p, float (&o)[8]) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+      o[2 * i] = __uint_as_float(v[i] << 16);
+      o[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+    }
+  }
   __device__ static __forceinline__ void load(const bf16_t* p, float (&o)[8]) {
     uint4 v = *reinterpret_cast<const uint4*>(p);
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
