@@ -166,6 +166,24 @@ int moe_dispatch(const moe_shape_t* shape, const void* X, const int32_t* topk_id
                  size_t ws_bytes, void* stream);
 
 /*
+ * moe_route_dispatch -- moe_route, moe_dispatch and (with aux_P, aux_loss != NULL) moe_aux_loss in one call
+ * of four kernels instead of seven: the gate of Eq. 3 and the counting of Algorithm 3's token assignment
+ * read the logits once.  Same arguments and the same results as the three calls: every integer output
+ * and topk_w bit for bit; aux_P and aux_loss up to the order of their fp32 sums (a fixed order, so two
+ * runs agree bit for bit).  aux_alpha is ignored when aux_P and aux_loss are NULL (they go together).
+ *   ws >= moe_route_dispatch_workspace_bytes(shape)
+ * moe_route_aux_bwd -- moe_route_bwd followed by moe_aux_loss_bwd(accumulate = 1) in one kernel:
+ *   dlogits = d(loss)/d(logits) through the combine weights (from dw) + dloss * d(aux loss)/d(logits).
+ */
+size_t moe_route_dispatch_workspace_bytes(const moe_shape_t* shape);
+int moe_route_dispatch(const moe_shape_t* shape, const float* logits, const void* X, float aux_alpha,
+                       int32_t* topk_idx, float* topk_w, int32_t* counts, int32_t* offsets, int32_t* row_of,
+                       int32_t* src_of, void* Xp, float* aux_P, float* aux_loss, void* ws, size_t ws_bytes,
+                       void* stream);
+int moe_route_aux_bwd(const moe_shape_t* shape, const float* logits, const int32_t* topk_idx, const float* dw,
+                      const int32_t* counts, float alpha, float dloss, float* dlogits, void* stream);
+
+/*
  * moe_dispatch_static -- moe_dispatch for callers that cannot allocate device memory or cannot hand over
  * a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
  * Same arguments, same kernels and same results as moe_dispatch, without `ws`: the per-chunk

@@ -20,7 +20,8 @@ EXPORTS = ["moe_abi_version", "moe_last_error", "moe_route_bwd", "moe_router_fwd
            "moe_combine", "moe_combine_bwd", "moe_profile_enable", "moe_profile_report", "moe_copy_probe",
            "moe_aux_loss_workspace_bytes", "moe_aux_loss", "moe_aux_loss_bwd",
            "moe_plan_overlap_degree", "moe_plan_predict_load", "moe_plan_materialize", "moe_plan_dispatch",
-           "moe_dispatch_static", "moe_mfma_probe", "moe_expert_fwd_gather", "moe_expert_bwd_gather"]
+           "moe_dispatch_static", "moe_mfma_probe", "moe_expert_fwd_gather", "moe_expert_bwd_gather",
+           "moe_route_dispatch_workspace_bytes", "moe_route_dispatch", "moe_route_aux_bwd"]
 
 
 class MoEError(RuntimeError):
@@ -102,6 +103,12 @@ def load_library():
     lib.moe_route_bwd.argtypes = [shp, vp, vp, vp, vp, vp]
     lib.moe_dispatch.restype = ctypes.c_int
     lib.moe_dispatch.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_route_dispatch_workspace_bytes.restype = sz
+    lib.moe_route_dispatch_workspace_bytes.argtypes = [shp]
+    lib.moe_route_dispatch.restype = ctypes.c_int
+    lib.moe_route_dispatch.argtypes = [shp, vp, vp, ctypes.c_float] + [vp] * 10 + [sz, vp]
+    lib.moe_route_aux_bwd.restype = ctypes.c_int
+    lib.moe_route_aux_bwd.argtypes = [shp, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, vp, vp]
     lib.moe_dispatch_static.restype = ctypes.c_int
     lib.moe_dispatch_static.argtypes = [shp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_expert_fwd.restype = ctypes.c_int
@@ -296,6 +303,32 @@ def moe_dispatch(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, 
     _check(rc, "moe_dispatch")
 
 
+def moe_route_dispatch_workspace_bytes(shape: MoEShape) -> int:
+    return int(load_library().moe_route_dispatch_workspace_bytes(ctypes.byref(shape.c())))
+
+
+def moe_route_dispatch(shape: MoEShape, logits, X, aux_alpha, topk_idx, topk_w, counts, offsets, row_of, src_of, Xp,
+                       aux_P, aux_loss, ws, stream=None):
+    """moe_route + moe_dispatch (+ moe_aux_loss when aux_P and aux_loss are given) in one call."""
+    dt = shape.torch_dtype
+    rc = load_library().moe_route_dispatch(
+        ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"), _ptr(X, dt, "X"), float(aux_alpha),
+        _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(topk_w, torch.float32, "topk_w"), _ptr(counts, torch.int32, "counts"),
+        _ptr(offsets, torch.int32, "offsets"), _ptr(row_of, torch.int32, "row_of"), _ptr(src_of, torch.int32, "src_of"),
+        _ptr(Xp, dt, "Xp"), _ptr(aux_P, torch.float32, "aux_P"), _ptr(aux_loss, torch.float32, "aux_loss"),
+        _ptr(ws, None, "ws"), ws.numel() * ws.element_size(), _stream(stream))
+    _check(rc, "moe_route_dispatch")
+
+
+def moe_route_aux_bwd(shape: MoEShape, logits, topk_idx, dw, counts, alpha, dloss, dlogits, stream=None):
+    """moe_route_bwd + moe_aux_loss_bwd(accumulate) in one kernel."""
+    rc = load_library().moe_route_aux_bwd(ctypes.byref(shape.c()), _ptr(logits, torch.float32, "logits"),
+                                          _ptr(topk_idx, torch.int32, "topk_idx"), _ptr(dw, torch.float32, "dw"),
+                                          _ptr(counts, torch.int32, "counts"), float(alpha), float(dloss),
+                                          _ptr(dlogits, torch.float32, "dlogits"), _stream(stream))
+    _check(rc, "moe_route_aux_bwd")
+
+
 def moe_dispatch_static(shape: MoEShape, X, topk_idx, counts, offsets, row_of, src_of, Xp, stream=None):
     """moe_dispatch without a workspace argument (the library's built-in scratch array; allocates nothing)."""
     dt = shape.torch_dtype
@@ -410,6 +443,8 @@ class MoEHotPath:
                 -> moe_route_bwd (gradient of the router logits)
     With aux_alpha > 0, forward() also evaluates the auxiliary load-balancing loss (moe_aux_loss, after
     the dispatch has counted the loads) and backward() adds its gradient to dlogits (moe_aux_loss_bwd).
+    With fused (the default), gate + dispatch + loss go through moe_route_dispatch and the two backward
+    calls of the gate through moe_route_aux_bwd: the same results from four launches fewer.
     No arithmetic happens here; tensors are only allocated and handed to the library.
 
     The shared experts depend on nothing the routed experts produce, so with overlap_shared their
@@ -419,9 +454,11 @@ class MoEHotPath:
     """
 
     def __init__(self, shape: MoEShape, n_shared: int = 0, d_ff_shared: int = 0, device="cuda:0",
-                 overlap_shared: bool = False, aux_alpha: float = 0.0, gather: bool = False):
+                 overlap_shared: bool = False, aux_alpha: float = 0.0, gather: bool = False, fused: bool = True):
         self.shape, self.S, self.Fs, self.device = shape, n_shared, d_ff_shared, torch.device(device)
         self.gather = bool(gather)  # routed experts read X and dY through src_of (moe_expert_*_gather)
+        # gate, dispatch and auxiliary loss through moe_route_dispatch / moe_route_aux_bwd (fewer launches)
+        self.fused = bool(fused)
         self.aux_alpha = float(aux_alpha)
         self.overlap = bool(overlap_shared and n_shared)
         s, dt, dev = shape, shape.torch_dtype, self.device
@@ -441,8 +478,8 @@ class MoEHotPath:
             "dWg_c": torch.empty(s.E, s.d, s.d_ff, **f), "dWu_c": torch.empty(s.E, s.d, s.d_ff, **f),
             "dWd_c": torch.empty(s.E, s.d_ff, s.d, **f),
         }
-        ws = max(moe_dispatch_workspace_bytes(s), moe_expert_fwd_workspace_bytes(s, s.E, A, False),
-                 moe_expert_bwd_workspace_bytes(s, s.E, A, False))
+        ws = max(moe_dispatch_workspace_bytes(s), moe_route_dispatch_workspace_bytes(s),
+                 moe_expert_fwd_workspace_bytes(s, s.E, A, False), moe_expert_bwd_workspace_bytes(s, s.E, A, False))
         if n_shared:
             self.sshape = dataclasses.replace(s, d_ff=d_ff_shared)
             S, Fs = n_shared, d_ff_shared
@@ -487,10 +524,15 @@ class MoEHotPath:
             main = self._fork(stream)
             moe_expert_fwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], b["Ysh"],
                            self.ws_shared, self.side)
-        moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
-        moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws, stream)
-        if self.aux_alpha > 0:
-            moe_aux_loss(s, logits, b["counts"], self.aux_alpha, b["aux_P"], b["aux_loss"], self.ws, stream)
+        if self.fused:
+            moe_route_dispatch(s, logits, X, self.aux_alpha, b["topk_idx"], b["topk_w"], b["counts"], b["offsets"],
+                               b["row_of"], b["src_of"], b["Xp"], b.get("aux_P"), b.get("aux_loss"), self.ws, stream)
+        else:
+            moe_route(s, logits, b["topk_idx"], b["topk_w"], stream)
+            moe_dispatch(s, X, b["topk_idx"], b["counts"], b["offsets"], b["row_of"], b["src_of"], b["Xp"], self.ws,
+                         stream)
+            if self.aux_alpha > 0:
+                moe_aux_loss(s, logits, b["counts"], self.aux_alpha, b["aux_P"], b["aux_loss"], self.ws, stream)
         if self.gather:
             moe_expert_fwd_gather(s, b["offsets"], b["src_of"], X, Wg, Wu, Wd, b["G"], b["U"], b["H"], b["Yp"], self.ws,
                                   stream)
@@ -525,7 +567,11 @@ class MoEHotPath:
             moe_expert_bwd(self.sshape, self.S, None, s.T, X, Wsg, Wsu, Wsd, b["Gs"], b["Us"], b["Hs"], dY, b["dXsh"],
                            b["s_active_ids"], b["s_n_active"], b["dWsg"], b["dWsu"], b["dWsd"], self.ws, stream)
         moe_combine(s, b["dXp"], b["row_of"], None, b["dXsh"] if self.S else None, b["dX"], stream)
-        moe_route_bwd(s, self._logits, b["topk_idx"], b["dw"], b["dlogits"], stream)
-        if self.aux_alpha > 0:
-            moe_aux_loss_bwd(s, self._logits, b["counts"], self.aux_alpha, 1.0, True, b["dlogits"], stream)
+        if self.fused and self.aux_alpha > 0:
+            moe_route_aux_bwd(s, self._logits, b["topk_idx"], b["dw"], b["counts"], self.aux_alpha, 1.0, b["dlogits"],
+                              stream)
+        else:
+            moe_route_bwd(s, self._logits, b["topk_idx"], b["dw"], b["dlogits"], stream)
+            if self.aux_alpha > 0:
+                moe_aux_loss_bwd(s, self._logits, b["counts"], self.aux_alpha, 1.0, True, b["dlogits"], stream)
         return b["dX"]

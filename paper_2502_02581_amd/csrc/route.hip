@@ -1,11 +1,12 @@
 // moe_route: the gate of Eq. 3 -- scores, top-k selection, renormalised combine weights.
 // One wavefront per token; lane l holds logits l, l+64, ...; each of the k rounds is a
 // wave-wide arg-max by xor-shuffles, so no LDS and no atomics are needed.
+#include "gate_device.h"
 #include "moe_common.h"
 
 namespace moe {
 
-template <int R>  // logits per lane, E <= 64*R
+template <int R>
 __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ logits,
                                                     int32_t* __restrict__ topk_idx,
                                                     float* __restrict__ topk_w, int T, int E, int k,
@@ -13,70 +14,12 @@ __global__ __launch_bounds__(256) void route_kernel(const float* __restrict__ lo
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
-  const float* row = logits + (size_t)t * E;
-  float v[R];
-#pragma unroll
-  for (int r = 0; r < R; r++) {
-    int e = lane + 64 * r;
-    v[r] = e < E ? row[e] : -INFINITY;
-  }
-  uint32_t taken = 0;
-#pragma unroll
-  for (int r = 0; r < R; r++)
-    if (lane + 64 * r >= E) taken |= 1u << r;
-
-  float sel_v = 0.f;
-  int sel_e = 0;
-  for (int j = 0; j < k; j++) {
-    float bv = -INFINITY;
-    int be = 0x7fffffff;
-#pragma unroll
-    for (int r = 0; r < R; r++) {
-      bool free_ = !((taken >> r) & 1u);
-      if (free_ && (be == 0x7fffffff || v[r] > bv)) {
-        bv = v[r];
-        be = lane + 64 * r;
-      }
-    }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) {
-      float ov = __shfl_xor(bv, m, kWave);
-      int oe = __shfl_xor(be, m, kWave);
-      bool other = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
-      if (other) {
-        bv = ov;
-        be = oe;
-      }
-    }
-    if ((be & 63) == lane) taken |= 1u << (be >> 6);
-    if (lane == j) {
-      sel_v = bv;
-      sel_e = be;
-    }
-  }
-  // scores of the selected experts
-  float p;
-  if (gate == MOE_GATE_SOFTMAX) {
-    float m = __shfl(sel_v, 0, kWave);  // the first selected logit is the row maximum
-    p = expf(sel_v - m);
-    if (!renorm) {
-      float s = 0.f;
-#pragma unroll
-      for (int r = 0; r < R; r++)
-        if (lane + 64 * r < E) s += expf(v[r] - m);
-      s = wave_sum(s);
-      p = p / s;
-    }
-  } else {
-    p = 1.f / (1.f + expf(-sel_v));
-  }
-  if (renorm) {
-    float s = wave_sum(lane < k ? p : 0.f);
-    p = p / s;
-  }
+  float v[R], w;
+  int e;
+  route_token<R>(logits + (size_t)t * E, lane, E, k, gate, renorm, v, e, w);
   if (lane < k) {
-    topk_idx[(size_t)t * k + lane] = sel_e;
-    topk_w[(size_t)t * k + lane] = p;
+    topk_idx[(size_t)t * k + lane] = e;
+    topk_w[(size_t)t * k + lane] = w;
   }
 }
 
@@ -156,39 +99,7 @@ __global__ __launch_bounds__(256) void route_bwd_kernel(const float* __restrict_
   }
 }
 
-// ---- auxiliary load-balancing loss: L = alpha E sum_e f_e P_e, f_e = counts[e] / (T k),
-// P_e = mean over tokens of expert e's share of the gate's scores (softmax, or sigmoid scores
-// divided by their sum over the E experts).  Same mapping as route_kernel: one wavefront per token,
-// lane l holds experts l, l + 64, ...
-template <int R>
-__device__ __forceinline__ void gate_shares(const float* __restrict__ row, int lane, int E, int gate, float (&s)[R],
-                                            float (&p)[R], float& inv_tot) {
-  float v[R];
-#pragma unroll
-  for (int r = 0; r < R; r++) v[r] = lane + 64 * r < E ? row[lane + 64 * r] : -INFINITY;
-  float tot = 0.f;
-  if (gate == MOE_GATE_SOFTMAX) {
-    float m = v[0];
-#pragma unroll
-    for (int r = 1; r < R; r++) m = fmaxf(m, v[r]);
-    m = wave_max(m);
-#pragma unroll
-    for (int r = 0; r < R; r++) {
-      s[r] = lane + 64 * r < E ? expf(v[r] - m) : 0.f;
-      tot += s[r];
-    }
-  } else {
-#pragma unroll
-    for (int r = 0; r < R; r++) {
-      s[r] = lane + 64 * r < E ? 1.f / (1.f + expf(-v[r])) : 0.f;
-      tot += s[r];
-    }
-  }
-  inv_tot = 1.f / wave_sum(tot);
-#pragma unroll
-  for (int r = 0; r < R; r++) p[r] = s[r] * inv_tot;
-}
-
+// ---- auxiliary load-balancing loss (gate_shares: gate_device.h)
 // Wave w sums the shares of tokens w, w + n_waves, ... in that order and writes its E partial sums:
 // no atomics, the same result on every run.
 template <int R>
@@ -278,6 +189,75 @@ __global__ __launch_bounds__(256) void aux_bwd_kernel(const float* __restrict__ 
   }
 }
 
+// The two backward kernels above in one pass over the logits: dlogits = (gate backward from dw) + dloss *
+// (gradient of the auxiliary loss with the loads held constant); every element is written once.
+template <int R>
+__global__ __launch_bounds__(256) void route_aux_bwd_kernel(const float* __restrict__ logits,
+                                                            const int32_t* __restrict__ topk_idx,
+                                                            const float* __restrict__ dw, const int32_t* __restrict__ counts,
+                                                            float* __restrict__ dlogits, int T, int E, int k, int gate,
+                                                            int renorm, float scale) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const float* row = logits + (size_t)t * E;
+  float v[R], raw[R], p[R], inv_tot;
+#pragma unroll
+  for (int r = 0; r < R; r++) v[r] = lane + 64 * r < E ? row[lane + 64 * r] : -INFINITY;
+  gate_shares_of<R>(v, lane, E, gate, raw, p, inv_tot);
+  // the gate's scores: the softmax itself (= the shares), or the sigmoid values
+  float s[R];
+#pragma unroll
+  for (int r = 0; r < R; r++) s[r] = gate == MOE_GATE_SOFTMAX ? p[r] : raw[r];
+  // ---- gate backward (as route_bwd_kernel): lane j < k holds the j-th selected expert
+  const int my_e = lane < k ? topk_idx[(size_t)t * k + lane] : -1;
+  const float my_dw = lane < k ? dw[(size_t)t * k + lane] : 0.f;
+  float my_s = 0.f;
+  for (int j = 0; j < k; j++) {  // fetch the score of every selected expert from the lane that owns it
+    const int e = __shfl(my_e, j, kWave);
+    float sv = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; r++)
+      if (lane + 64 * r == e) sv = s[r];
+    sv = __shfl(sv, e & 63, kWave);
+    if (lane == j) my_s = sv;
+  }
+  float my_ds = my_dw;
+  if (renorm) {
+    const float tot = wave_sum(my_s);
+    const float c = wave_sum(my_dw * my_s) / tot;
+    my_ds = lane < k ? (my_dw - c) / tot : 0.f;
+  }
+  const float dot = gate == MOE_GATE_SOFTMAX ? wave_sum(my_s * my_ds) : 0.f;
+  float ds[R];
+#pragma unroll
+  for (int r = 0; r < R; r++) ds[r] = 0.f;
+  for (int j = 0; j < k; j++) {
+    const int e = __shfl(my_e, j, kWave);
+    const float g = __shfl(my_ds, j, kWave);
+#pragma unroll
+    for (int r = 0; r < R; r++)
+      if (lane + 64 * r == e) ds[r] = g;
+  }
+  // ---- auxiliary loss (as aux_bwd_kernel): c_e = scale * counts[e]
+  float c[R], adot = 0.f;
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    c[r] = lane + 64 * r < E ? scale * (float)counts[lane + 64 * r] : 0.f;
+    adot += p[r] * c[r];
+  }
+  adot = wave_sum(adot);
+#pragma unroll
+  for (int r = 0; r < R; r++) {
+    const int e = lane + 64 * r;
+    if (e < E) {
+      const float dz = gate == MOE_GATE_SOFTMAX ? s[r] * (ds[r] - dot) : ds[r] * s[r] * (1.f - s[r]);
+      const float az = gate == MOE_GATE_SOFTMAX ? p[r] * (c[r] - adot) : (c[r] - adot) * inv_tot * raw[r] * (1.f - raw[r]);
+      dlogits[(size_t)t * E + e] = dz + az;
+    }
+  }
+}
+
 static int aux_waves(int T) { return T < 256 ? T : 256; }
 
 }  // namespace moe
@@ -286,15 +266,6 @@ extern "C" size_t moe_aux_loss_workspace_bytes(const moe_shape_t* shape) {
   if (!shape || shape->T < 0 || shape->E < 1) return 0;
   return (size_t)moe::aux_waves(shape->T) * (size_t)shape->E * sizeof(float) + 256;
 }
-
-#define MOE_BY_EXPERTS(E, CALL) \
-  do {                          \
-    if ((E) <= 64) CALL(1);     \
-    else if ((E) <= 128) CALL(2); \
-    else if ((E) <= 256) CALL(4); \
-    else if ((E) <= 512) CALL(8); \
-    else CALL(16);              \
-  } while (0)
 
 extern "C" int moe_aux_loss(const moe_shape_t* shape, const float* logits, const int32_t* counts, float alpha, float* P,
                             float* loss, void* ws, size_t ws_bytes, void* stream) {
@@ -398,4 +369,27 @@ extern "C" int moe_route(const moe_shape_t* shape, const float* logits, int32_t*
   else MOE_ROUTE(16);
 #undef MOE_ROUTE
   return launch_status("moe_route");
+}
+
+extern "C" int moe_route_aux_bwd(const moe_shape_t* shape, const float* logits, const int32_t* topk_idx, const float* dw,
+                                 const int32_t* counts, float alpha, float dloss, float* dlogits, void* stream) {
+  using namespace moe;
+  int rc = check_shape(shape, "moe_route_aux_bwd");
+  if (rc) return rc;
+  if (shape->T == 0) return MOE_OK;  // nothing to do (empty tensors may be null)
+  if (!logits || !topk_idx || !dw || !counts || !dlogits) {
+    set_error("moe_route_aux_bwd: null pointer");
+    return MOE_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int T = shape->T, E = shape->E;
+  const float scale = dloss * alpha * (float)E / ((float)T * (float)shape->k) / (float)T;
+  dim3 grid((T + 3) / 4), block(256);
+  ProfScope prof("route_bwd_kernel", st);
+#define MOE_ROUTE_AUX_BWD(R)                                                                                        \
+  hipLaunchKernelGGL(route_aux_bwd_kernel<R>, grid, block, 0, st, logits, topk_idx, dw, counts, dlogits, T, E, shape->k, \
+                     shape->gate, shape->renorm, scale)
+  MOE_BY_EXPERTS(E, MOE_ROUTE_AUX_BWD);
+#undef MOE_ROUTE_AUX_BWD
+  return launch_status("moe_route_aux_bwd");
 }

@@ -572,3 +572,65 @@ def test_step_replayed_from_a_hip_graph():
             if k in ("dWg_c", "dWd_c"):
                 a, b = a[:n_act], b[:n_act]
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, k)
+
+
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (517, 8, 8), (517, 64, 3), (300, 65, 2), (1500, 256, 8), (2100, 300, 6),
+                                   (8192, 256, 8), (77, 1024, 64), (1000, 60, 5)])
+@pytest.mark.parametrize("gate", ["softmax", "sigmoid"])
+def test_fused_prologue_matches_separate_calls(T, E, k, gate):
+    """moe_route_dispatch against moe_route + moe_dispatch + moe_aux_loss, and moe_route_aux_bwd against
+    moe_route_bwd + moe_aux_loss_bwd: integers, combine weights and copied rows bit for bit, the loss terms
+    to fp32 summation order; everything against the oracle as well."""
+    import paper_2502_02581_amd as moe
+
+    cfg = small_cfg(T=T, d=16, E=E, k=k, d_ff=8, zipf_s=1.2, seed=13, dtype="bf16")
+    lg = wl.make_logits(cfg)
+    shape = moe.MoEShape(T, 16, E, k, 8, "bf16", gate, True)
+    dev = "cuda"
+    alpha = 0.01
+    X = wl.make_tokens(cfg).to(dev)
+    lgd = lg.to(dev)
+
+    def bufs():
+        i32 = dict(dtype=torch.int32, device=dev)
+        return {"topk_idx": torch.full((T, k), -3, **i32), "topk_w": torch.full((T, k), float("nan"), device=dev),
+                "counts": torch.full((E,), -3, **i32), "offsets": torch.full((E + 1,), -3, **i32),
+                "row_of": torch.full((T * k,), -3, **i32), "src_of": torch.full((T * k,), -3, **i32),
+                "Xp": torch.full((T * k, 16), float("nan"), dtype=torch.bfloat16, device=dev),
+                "P": torch.full((E,), float("nan"), device=dev), "L": torch.full((1,), float("nan"), device=dev)}
+
+    a, b = bufs(), bufs()
+    ws = torch.empty(max(moe.moe_dispatch_workspace_bytes(shape), moe.moe_aux_loss_workspace_bytes(shape),
+                         moe.moe_route_dispatch_workspace_bytes(shape)), dtype=torch.uint8, device=dev)
+    moe.moe_route(shape, lgd, a["topk_idx"], a["topk_w"])
+    moe.moe_dispatch(shape, X, a["topk_idx"], a["counts"], a["offsets"], a["row_of"], a["src_of"], a["Xp"], ws)
+    moe.moe_aux_loss(shape, lgd, a["counts"], alpha, a["P"], a["L"], ws)
+    ws.fill_(255)
+    moe.moe_route_dispatch(shape, lgd, X, alpha, b["topk_idx"], b["topk_w"], b["counts"], b["offsets"], b["row_of"],
+                           b["src_of"], b["Xp"], b["P"], b["L"], ws)
+    torch.cuda.synchronize()
+    for key in ("topk_idx", "topk_w", "counts", "offsets", "row_of", "src_of", "Xp"):
+        assert torch.equal(a[key].view(torch.uint8), b[key].view(torch.uint8)), key
+    ridx, rw = orc.route(lg.numpy(), k, gate, True)
+    assert np.array_equal(b["topk_idx"].cpu().numpy(), ridx)
+    rc = orc.dispatch_plan(ridx, E)
+    assert np.array_equal(b["counts"].cpu().numpy(), rc[0]) and np.array_equal(b["row_of"].cpu().numpy(), rc[2])
+    L_ref, P_ref = orc.aux_loss(lg.numpy(), rc[0], k, alpha, gate)
+    assert scale_rel_err(b["P"].cpu(), P_ref) <= 1e-4 and scale_rel_err(a["P"].cpu(), P_ref) <= 1e-4
+    assert abs(float(b["L"].item()) - L_ref) <= 1e-4 * abs(L_ref)
+    # without the loss: P and L are not touched
+    c = bufs()
+    moe.moe_route_dispatch(shape, lgd, X, 0.0, c["topk_idx"], c["topk_w"], c["counts"], c["offsets"], c["row_of"],
+                           c["src_of"], c["Xp"], None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(c["row_of"], a["row_of"]) and bool(torch.isnan(c["P"]).all())
+    # backward of the gate with the loss folded in
+    dw = torch.randn(T, k, generator=torch.Generator().manual_seed(3)).to(dev)
+    sep = torch.full((T, E), float("nan"), device=dev)
+    fus = torch.full((T, E), float("nan"), device=dev)
+    moe.moe_route_bwd(shape, lgd, a["topk_idx"], dw, sep)
+    moe.moe_aux_loss_bwd(shape, lgd, a["counts"], alpha, 1.7, True, sep)
+    moe.moe_route_aux_bwd(shape, lgd, a["topk_idx"], dw, a["counts"], alpha, 1.7, fus)
+    torch.cuda.synchronize()
+    ref = orc.route_bwd(lg.numpy(), ridx, dw.cpu().numpy(), gate, True) + orc.aux_loss_bwd(lg.numpy(), rc[0], k, alpha, gate, 1.7)
+    assert scale_rel_err(fus.cpu(), ref) <= 1e-4 and scale_rel_err(sep.cpu(), ref) <= 1e-4
