@@ -297,12 +297,14 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
     if (kAuxLoads == 2) a.r[kAuxLoads > 1 ? 1 : 0] = *reinterpret_cast<const uint4*>((const T*)p.in[1] + off);
     return a;
   };
+  // (all stores carry the streaming hint: every output here is read again only by a later kernel, after
+  // gigabytes of other traffic; 2-3 % on the row GEMMs of the Qwen- and stress-shaped workloads)
   auto body = [&](int m, int n, const auto& v, const Aux* aux) __attribute__((always_inline)) {
     constexpr int W = sizeof(v[0]) / sizeof(float);
     if (m >= rows || n >= n_valid) return;
     const int64_t off = (int64_t)(c_row0 + m) * p.ldc + n0 + n;
     if (EPI == EPI_STORE) {
-      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, v[0]);
     } else if (EPI == EPI_STORE_F32) {  // fp32 output whatever the operand type (router logits)
       Pack<float, W>::store((float*)p.out[0] + off, v[0]);
     } else if (EPI == EPI_ADD) {        // accumulate into the output
@@ -311,13 +313,13 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       else Pack<T, W>::load((const T*)p.out[0] + off, o);
 #pragma unroll
       for (int q = 0; q < W; q++) o[q] += v[0][q];
-      Pack<T, W>::store((T*)p.out[0] + off, o);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, o);
     } else if (EPI == EPI_GELU_FWD) {    // two-matrix expert: keep the pre-activation, store f of it
       float h[W];
 #pragma unroll
       for (int q = 0; q < W; q++) h[q] = gelu_f<T>(v[0][q]);
-      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
-      Pack<T, W>::store((T*)p.out[2] + off, h);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store_nt((T*)p.out[2] + off, h);
     } else if (EPI == EPI_GELU_BWD) {    // dZ = dH f'(Z)
       float z[W], dz[W];
       if (aux) Pack<T, W>::widen(aux->r[0], z);
@@ -325,14 +327,14 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
       const float sc = p.c_scale ? p.c_scale[p.a_index[a_row0 + m]] : 1.f;
 #pragma unroll
       for (int q = 0; q < W; q++) dz[q] = sc * v[0][q] * gelu_grad_f<T>(z[q]);
-      Pack<T, W>::store((T*)p.out[0] + off, dz);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, dz);
     } else if (EPI == EPI_SWIGLU_FWD) {
       float h[W];
 #pragma unroll
       for (int q = 0; q < W; q++) h[q] = v[0][q] * sigmoidf_<T>(v[0][q]) * v[NB - 1][q];
-      Pack<T, W>::store((T*)p.out[0] + off, v[0]);
-      Pack<T, W>::store((T*)p.out[1] + off, v[NB - 1]);
-      Pack<T, W>::store((T*)p.out[2] + off, h);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, v[0]);
+      Pack<T, W>::store_nt((T*)p.out[1] + off, v[NB - 1]);
+      Pack<T, W>::store_nt((T*)p.out[2] + off, h);
     } else {
       float g[W], u[W], dg[W], du[W];
       if (aux) {
@@ -350,8 +352,8 @@ __device__ __forceinline__ void row_gemm_tile(const RowGemm& p, const RowTile& t
         du[q] = dh * g[q] * s;
         dg[q] = dh * u[q] * s * (1.f + g[q] * (1.f - s));
       }
-      Pack<T, W>::store((T*)p.out[0] + off, dg);
-      Pack<T, W>::store((T*)p.out[1] + off, du);
+      Pack<T, W>::store_nt((T*)p.out[0] + off, dg);
+      Pack<T, W>::store_nt((T*)p.out[1] + off, du);
     }
   };
   if constexpr (kAuxLoads > 0) {
