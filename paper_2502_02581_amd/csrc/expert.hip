@@ -494,7 +494,7 @@ template <> struct Cores<PATH_BF16_DMA> {
   template <int NB> using core_light = MfmaDmaCore<128, 128, NB, false, false, 2, 2, 0>;
 };
 constexpr int kLightGroupRows = 256;  // groups up to this many rows take the light dW kernel
-constexpr int kLightReps = 8;         // column tiles per block of that kernel
+constexpr int kLightReps = 2;         // column tiles per block of that kernel (1: +5 % time on the DeepSeek shape, 8: +3 %)
 
 // The tile cores a row-tiled GEMM launch may use: one for the fp32 and the general bf16 path, four
 // heights (256, 128, 64, 32 rows) for the DMA path so that ragged groups waste little MFMA work.
