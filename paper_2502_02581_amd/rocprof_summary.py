@@ -23,6 +23,8 @@ import re
 
 def short_name(n: str) -> str:
     n = re.sub(r"void at::native::.*?distribution.*", "at::native::distribution_elementwise (torch.randn: input generation, untimed)", n)
+    if n.startswith("__amd_rocclr_copyBuffer"):
+        n += " (the runtime's staged host<->device copies: inputs up, sampled outputs down; untimed)"
     n = n.replace("void moe::", "moe::")
     return n if len(n) < 220 else n[:217] + "..."
 
