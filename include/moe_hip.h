@@ -123,7 +123,7 @@ int moe_route_bwd(const moe_shape_t* shape, const float* logits, const int32_t* 
 
 /*
  * moe_aux_loss / moe_aux_loss_bwd -- the auxiliary load-balancing loss the paper's evaluation
- * setup trains with (Section 6, experimental setup: weight 0.001; its sensitivity study sweeps the
+ * setup trains with (Section 5.1, experimental setup: weight 0.001; its sensitivity study sweeps the
  * weight to 0.1).  The paper cites the loss and does not print it; this is the product form of that
  * family:
  *   L = alpha * E * sum_e f_e * P_e,   f_e = counts[e] / (T k),   P_e = (1/T) sum_t p_te,

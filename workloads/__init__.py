@@ -90,6 +90,9 @@ CONFIGS.update({
     "gpt-l": MoEConfig("gpt-l", T=8192, d=1536, E=64, k=2, d_ff=6144, ffn="gelu", zipf_s=1.0, aux_alpha=AUX_ALPHA),
 })
 
+# The paper's top-k sweep (sensitivity study of Section 5.4: Qwen1.5-MoE with k = 2 ... 5); k = 4 is "qwen" itself.
+CONFIGS.update({"qwen-k%d" % k: dataclasses.replace(CONFIGS["qwen"], name="qwen-k%d" % k, k=k) for k in (2, 3, 5)})
+
 WEIGHT_STD = 0.02
 TOKEN_STD = 0.02
 GRAD_STD = 0.02
