@@ -693,10 +693,11 @@ static void expert_bwd_impl(const BwdArgs& a, hipStream_t st) {
     // groups with few rows are bound by writing their gradient, not by MFMA work: they go to a
     // kernel that keeps several blocks per CU in flight
     if (!shared) {
-      w.k_min = v.k_min = kLightGroupRows + 1;
+      const int light_rows = MOE_KNOB("MOE_LIGHT_ROWS", kLightGroupRows);
+      w.k_min = v.k_min = light_rows + 1;
       WGemm wl_ = w, vl_ = v;
       wl_.k_min = vl_.k_min = 1;
-      wl_.k_max = vl_.k_max = kLightGroupRows;
+      wl_.k_max = vl_.k_max = light_rows;
       // column tiles per block: at most kLightReps, and the same for every block of a row of tiles (11
       // column tiles go 6 + 5, not 8 + 3: consecutive blocks run on different XCDs, and unequal blocks
       // would load the XCDs unequally)
